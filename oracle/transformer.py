@@ -1,0 +1,131 @@
+"""Oracle: Llama-style decoder forward with a KV cache (test infrastructure only).
+
+The paper treats the two models as black boxes M_p(.), M_q(.) that return next-token
+logits from one forward (Section 2, "Notations"); it names Llama-family decoders in
+bf16 (Section 4.1, App. C model table).  This file writes that forward out plainly:
+RMSNorm -> QKV -> RoPE -> causal attention over the cache (grouped-query) -> output
+projection + residual -> RMSNorm -> SwiGLU FFN + residual; final RMSNorm -> LM head.
+
+All matrices are [out_features, in_features] (y = x @ W.T).  Arithmetic runs in the
+dtype of `Model.dtype` (float32 by default, float64 for pins).
+"""
+from __future__ import annotations
+
+import numpy as np
+
+
+class Model:
+    """Weights of one decoder.  `w` mirrors the generator's dict layout, as NumPy arrays."""
+
+    def __init__(self, w: dict, n_heads: int, n_kv_heads: int, head_dim: int,
+                 rope_theta: float = 10000.0, rms_eps: float = 1e-5, dtype=np.float32):
+        self.dtype = dtype
+        cv = lambda a: np.ascontiguousarray(np.asarray(a, dtype=dtype))
+        self.tok_embed = cv(w["tok_embed"])
+        self.lm_head = cv(w["lm_head"])
+        self.final_norm = cv(w["final_norm"])
+        self.layers = [{k: cv(v) for k, v in lay.items()} for lay in w["layers"]]
+        self.n_heads, self.n_kv_heads, self.head_dim = n_heads, n_kv_heads, head_dim
+        self.rope_theta, self.rms_eps = rope_theta, rms_eps
+        self.vocab, self.d_model = self.tok_embed.shape
+
+
+class KVCache:
+    """Per-layer keys/values of the tokens fed so far.  Rollback only shortens `len`."""
+
+    def __init__(self, model: Model, max_len: int):
+        L, H, D = len(model.layers), model.n_kv_heads, model.head_dim
+        self.k = np.zeros((L, max_len, H, D), dtype=model.dtype)
+        self.v = np.zeros((L, max_len, H, D), dtype=model.dtype)
+        self.len = 0
+
+    def rollback(self, new_len: int):
+        if not 0 <= new_len <= self.len:
+            raise ValueError("rollback target outside [0, len]")
+        self.len = new_len
+
+
+def rmsnorm(x, gain, eps):
+    """x / sqrt(mean(x^2) + eps) * gain, per row."""
+    ms = np.mean(x * x, axis=-1, keepdims=True)
+    return x / np.sqrt(ms + x.dtype.type(eps)) * gain
+
+
+def rope(x, positions, theta):
+    """Rotate pairs (i, i + D/2) of the last axis by angle pos * theta^(-2i/D).  x: [M, H, D]."""
+    D = x.shape[-1]
+    half = D // 2
+    i = np.arange(half, dtype=np.float64)
+    inv_freq = theta ** (-2.0 * i / D)
+    ang = np.asarray(positions, dtype=np.float64)[:, None] * inv_freq[None, :]      # [M, half]
+    c = np.cos(ang).astype(x.dtype)[:, None, :]
+    s = np.sin(ang).astype(x.dtype)[:, None, :]
+    a, b = x[..., :half], x[..., half:]
+    return np.concatenate([a * c - b * s, a * s + b * c], axis=-1)
+
+
+def silu(x):
+    return x / (1.0 + np.exp(-x))
+
+
+def forward(model: Model, cache: KVCache, tokens) -> np.ndarray:
+    """Feed M new tokens at positions cache.len .. cache.len+M-1; return logits [M, vocab].
+
+    Row i is the logit vector of the token that follows tokens[i] (it attends to
+    everything in the cache plus tokens[0..i]).
+    """
+    tokens = np.asarray(tokens, dtype=np.int64)
+    M = tokens.shape[0]
+    n = cache.len
+    if n + M > cache.k.shape[1]:
+        raise ValueError("KV cache overflow")
+    H, Hkv, D = model.n_heads, model.n_kv_heads, model.head_dim
+    group = H // Hkv
+    pos = np.arange(n, n + M)
+    scale = model.dtype(1.0 / np.sqrt(D))
+    h = model.tok_embed[tokens]                                   # [M, d]
+    for l, w in enumerate(model.layers):
+        a = rmsnorm(h, w["attn_norm"], model.rms_eps)
+        q = (a @ w["wq"].T).reshape(M, H, D)
+        k = (a @ w["wk"].T).reshape(M, Hkv, D)
+        v = (a @ w["wv"].T).reshape(M, Hkv, D)
+        q = rope(q, pos, model.rope_theta)
+        k = rope(k, pos, model.rope_theta)
+        cache.k[l, n:n + M] = k
+        cache.v[l, n:n + M] = v
+        o = np.zeros((M, H, D), dtype=model.dtype)
+        for i in range(M):
+            T = n + i + 1                                          # token i sees positions 0..n+i
+            for j in range(H):
+                kv = j // group
+                s = (cache.k[l, :T, kv] @ q[i, j]) * scale        # [T]
+                s = s - s.max()
+                p = np.exp(s)
+                p = p / p.sum()
+                o[i, j] = p @ cache.v[l, :T, kv]
+        h = h + o.reshape(M, H * D) @ w["wo"].T
+        b = rmsnorm(h, w["ffn_norm"], model.rms_eps)
+        z = silu(b @ w["w_gate"].T) * (b @ w["w_up"].T)
+        h = h + z @ w["w_down"].T
+    cache.len = n + M
+    return rmsnorm(h, model.final_norm, model.rms_eps) @ model.lm_head.T
+
+
+class CachedModel:
+    """A model plus its cache, with the feed / rollback interface the loops use."""
+
+    def __init__(self, model: Model, max_len: int):
+        self.model = model
+        self.cache = KVCache(model, max_len)
+        self.n_forwards = 0
+
+    @property
+    def len(self) -> int:
+        return self.cache.len
+
+    def feed(self, tokens) -> np.ndarray:
+        self.n_forwards += 1
+        return forward(self.model, self.cache, tokens)
+
+    def rollback(self, new_len: int):
+        self.cache.rollback(new_len)
