@@ -1,0 +1,205 @@
+/*
+ * spec.h - C ABI of the MI355X (gfx950) library for parallel speculative decoding (PEARL).
+ *
+ * One context holds a target model M_p and a draft model M_q (paper, Section 2 "Notations"),
+ * a paged KV cache per model, a cache of draft distributions q_i (Algorithm 2, "retrieval of
+ * q_1..q_gamma from the cache") and two HIP streams so that drafting and verification overlap
+ * (Section 3.4 "Parallelism").  All arithmetic of the decoding path runs in this library's
+ * kernels; callers only provide device memory for the weights and the two streams.
+ *
+ * Conventions
+ *   - every function returns 0 (SPEC_OK) or a negative SPEC_E_* code and never throws or aborts;
+ *     spec_last_error() gives a message for the last failure of the calling thread.
+ *   - "device" pointers are HIP device memory on the current device, "host" pointers are
+ *     ordinary host memory.  Weights and streams are BORROWED: they must outlive the context.
+ *   - a context is not thread-safe; calls on one context must come from one thread at a time.
+ *   - uniform random numbers are inputs (host floats in (0,1)), never drawn inside the library.
+ *
+ * Weight layouts (all bf16)
+ *   - tok_embed      : row-major [vocab][d_model]
+ *   - norm gains     : [d_model]
+ *   - projections    : "panel-packed" (see spec_pack_weight).  A projection y = x W^T with
+ *                      W [N][K] is stored as N/16 panels; wqkv is the concatenation of the
+ *                      panels of W_q, W_k, W_v; w_gateup interleaves panels (gate panel j at
+ *                      2j, up panel j at 2j+1).
+ */
+#ifndef SPEC_H
+#define SPEC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  SPEC_OK = 0,
+  SPEC_E_INVAL = -1, /* bad argument; nothing was changed                         */
+  SPEC_E_NOMEM = -2, /* KV pages or device memory exhausted; state left unchanged  */
+  SPEC_E_STATE = -3, /* call not valid in the current state (e.g. no prefill yet)  */
+  SPEC_E_HIP = -4    /* a HIP call failed; the context should be freed             */
+};
+
+enum { SPEC_TARGET = 0, SPEC_DRAFT = 1 };
+
+/* Which acceptance step to run (spec_accept). */
+enum {
+  SPEC_ACCEPT_AR = 0,   /* no draft: draw the next token from row 0 of the last target forward      */
+  SPEC_ACCEPT_SD = 1,   /* vanilla speculative decoding, Section 2: rows p_1..p_{g+1} test x_1..x_g */
+  SPEC_ACCEPT_PRE = 2,  /* pre-verify, Section 3.2 / Algorithm 2: row p = M_p(x) tests x_1          */
+  SPEC_ACCEPT_POST = 3  /* post-verify, Section 3.3 / Algorithm 2: row P_i tests x_{i+1}, i=1..g   */
+};
+enum { SPEC_MODE_PRE = 0, SPEC_MODE_POST = 1 };
+
+#define SPEC_MAX_TOKENS 32 /* most tokens one forward may take (gamma_max + 1 <= SPEC_MAX_TOKENS) */
+
+typedef struct spec_ctx spec_ctx;
+
+typedef struct {
+  int n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ffn, vocab;
+  float rope_theta, rms_eps;
+} spec_model_desc;
+
+/* Device pointers, bf16.  Per-layer arrays are host arrays of n_layers device pointers. */
+typedef struct {
+  const void* tok_embed;
+  const void* final_norm;
+  const void* lm_head;        /* packed [vocab][d_model]                       */
+  const void* const* attn_norm;
+  const void* const* wqkv;    /* packed [(n_heads + 2 n_kv_heads) head_dim][d_model] */
+  const void* const* wo;      /* packed [d_model][n_heads head_dim]            */
+  const void* const* ffn_norm;
+  const void* const* w_gateup;/* packed, gate/up panels interleaved, [2 d_ffn][d_model] */
+  const void* const* w_down;  /* packed [d_model][d_ffn]                       */
+} spec_weights;
+
+typedef struct {
+  int gamma_max;      /* largest window size gamma that will be used (1..SPEC_MAX_TOKENS-1) */
+  int max_seq;        /* most tokens (prompt + generated + 2 gamma_max of speculation) a cache must hold */
+  int page_tokens;    /* tokens per KV page: 64                                             */
+  float temperature;  /* 0 = greedy (distributions become one-hot at the arg-max)           */
+  float logit_scale;  /* logits are multiplied by this before the softmax                   */
+  void* stream_target;/* hipStream_t, borrowed                                              */
+  void* stream_draft; /* hipStream_t, borrowed; may equal stream_target (serialised)        */
+} spec_config;
+
+/* ---- the decoding path --------------------------------------------------------------- */
+
+/* Build a context: allocates KV pages, activation scratch, the q cache and events on the
+ * current device.  Both models must have the same vocabulary.  SPEC_E_INVAL on unsupported
+ * shapes (head_dim not 64/128, sizes not multiples of 16/8), SPEC_E_NOMEM if allocation fails. */
+int spec_init(const spec_config* cfg, const spec_model_desc* target, const spec_weights* tw,
+              const spec_model_desc* draft, const spec_weights* dw, spec_ctx** out);
+void spec_free(spec_ctx* ctx);
+
+/* Reset both caches and feed prompt[0..n-2] to both models; prompt[n-1] becomes the frontier
+ * (the last committed token, the one token neither cache holds yet); mode := pre-verify.
+ * This realises "M_p(x), M_q(x) on the prefix" of Algorithm 2 with a KV cache.  Synchronous.
+ * `which_mask`: bit SPEC_TARGET / bit SPEC_DRAFT select the models to prefill (3 = both). */
+int spec_prefill(spec_ctx* ctx, const int32_t* prompt_host, int n_prompt, int which_mask);
+
+/* One drafting forward, asynchronous on the draft stream: q_i = M_q(x + [x_1..x_{i-1}]),
+ * x_i ~ q_i by inverse CDF with the uniform u (Algorithm 2, drafting loops).  The first call
+ * after an acceptance feeds the committed tokens the draft cache lacks (normally just the
+ * frontier); later calls feed the previously drafted token, which never leaves the device.
+ * q_i and x_i are appended to the q cache.  If tok_out_host is not NULL the call synchronises
+ * and returns x_i (tests only).  SPEC_E_STATE after 2*gamma_max unverified drafts. */
+int spec_draft_step(spec_ctx* ctx, float u, int32_t* tok_out_host);
+
+/* One target forward over n_tokens tokens against the KV cache, asynchronous on the target
+ * stream ("the target model verifies these draft tokens in parallel within a single forward",
+ * Section 1; rows p_1..p_n of Section 2).  tokens_host == NULL selects the tokens the step
+ * needs: the frontier followed by the first n_tokens-1 unverified drafts (these are read on
+ * the device; the target stream waits for the draft stream first).  If logits_out_host is not
+ * NULL the call synchronises and copies the fp32 logits [n_tokens][vocab] (tests only). */
+int spec_verify(spec_ctx* ctx, const int32_t* tokens_host, int n_tokens, float* logits_out_host);
+
+/* Speculative-sampling accept / reject on the device (Eq. (1): accept x iff r <= p[x]/q[x];
+ * on the first rejection draw from norm(max(0, p - q)); Section 2 and Algorithm 2), then the
+ * bookkeeping of the step.  Waits for both streams.  r_host[0..n_r-1] are the acceptance
+ * uniforms in test order, u_resample draws the corrected / bonus / autoregressive token.
+ * Outputs: *n_accepted draft tokens accepted; tokens_out_host[0..*n_out-1] the tokens committed
+ * by this step (at most gamma_max + 1); *next_mode the strategy of the next PEARL step.
+ * After the call the frontier is the last committed token.  *keep_len is -1 when the caches stay
+ * as they are (drafts still pending), otherwise the caller must cut every cache that holds more
+ * than *keep_len (= committed - 1) tokens back to that length with spec_rollback_kv.
+ * `force_mask`: < 0 = real decisions; otherwise bit i overrides the i-th decision (1 = accept)
+ * - measurement and scripted tests only. */
+int spec_accept(spec_ctx* ctx, int kind, const float* r_host, int n_r, float u_resample, long long force_mask,
+                int* n_accepted, int32_t* tokens_out_host, int* n_out, int* next_mode, int* keep_len);
+
+/* Drop everything after the first new_len tokens of one model's cache: O(1) - sets the length
+ * and returns whole pages to the pool (Figure 3: "drops x10, x11, x12").  Unverified drafts that
+ * lie beyond the new length are forgotten.  SPEC_E_INVAL if new_len > current length. */
+int spec_rollback_kv(spec_ctx* ctx, int which, int new_len);
+
+/* Forget every unverified draft token and its q row (the caller rolls the draft cache back itself). */
+int spec_drop_drafts(spec_ctx* ctx);
+
+int spec_kv_len(const spec_ctx* ctx, int which);     /* tokens currently in that model's cache */
+int spec_committed_len(const spec_ctx* ctx);         /* prompt + committed generated tokens    */
+int spec_kv_free_pages(const spec_ctx* ctx, int which);
+long long spec_forward_count(const spec_ctx* ctx, int which); /* forwards run so far by that model */
+
+/* Whole loops on top of the calls above (host control flow only): Algorithm 1/2 (algo 2), vanilla
+ * speculative decoding (algo 1), autoregressive decoding (algo 0).  Uniform arrays are indexed
+ * by step: u_draft[t*gamma + i], r_accept[t*(gamma+1) + i], u_resample[t]; each must hold
+ * n_generate steps.  force_alpha < 0 uses real decisions; otherwise decision (t, i) is taken
+ * from force_bits[t*(gamma+1)+i] (measurement only).  out_tokens_host receives n_generate tokens.
+ * stats_host (nullable, 8 doubles): steps, committed, draft forwards, target forwards,
+ * accepted, tested, post-verify steps, seconds. */
+int spec_generate(spec_ctx* ctx, int algo, int gamma, int n_generate, const float* u_draft,
+                  const float* r_accept, const float* u_resample, const uint8_t* force_bits,
+                  int32_t* out_tokens_host, double* stats_host);
+
+const char* spec_last_error(void);
+
+/* ---- set-up helpers and single kernels (tests, benchmarks) ------------------------------ */
+
+/* Repack a row-major bf16 matrix W[N][K] (device) into 16-row panels for the projection
+ * kernels.  Panel j of this matrix is written as panel (panel_start + j*panel_step) of dst;
+ * one panel is K_pad/32 blocks of 1 KiB (K_pad = K rounded up to 32, zero filled), block t
+ * holding for lane l = 16*(kk/8) + row the eight values W[16 j + row][32 t + kk .. +7].
+ * N % 16 == 0 and K % 8 == 0 are required.  Asynchronous on `stream`. */
+int spec_pack_weight(void* dst_dev, const void* src_dev, int N, int K, int panel_start, int panel_step,
+                     void* stream);
+size_t spec_packed_bytes(int N, int K);
+
+/* y[M][N] (fp32, device) = x[M][K] (bf16 row-major, device) * W^T with W panel-packed.
+ * The same kernel the forward uses; `work_dev` needs spec_gemm_workspace_bytes(M, N, K).
+ * M <= SPEC_MAX_TOKENS.  Asynchronous on `stream`. */
+int spec_gemm(float* y_dev, const void* x_dev, const void* w_packed_dev, int M, int N, int K,
+              void* work_dev, void* stream);
+size_t spec_gemm_workspace_bytes(int M, int N, int K);
+/* Only the streaming kernel of spec_gemm (no reduction pass); used to time it in isolation. */
+int spec_gemm_partials(const void* x_dev, const void* w_packed_dev, int M, int N, int K,
+                       void* work_dev, void* stream);
+
+/* Streaming-read probe: sums `bytes` bytes of device memory with 16-byte loads; used to
+ * measure the achievable HBM read ceiling next to the nominal peak.  out_dev: 4 bytes. */
+int spec_read_probe(const void* src_dev, size_t bytes, void* out_dev, void* stream);
+
+/* Fused scale -> softmax -> inverse-CDF draw on one fp32 logits row (device):
+ * writes the distribution to q_out_dev[vocab] and the token to tok_out_dev[0]. */
+int spec_sample_row(const float* logits_dev, int vocab, float temperature, float logit_scale, float u,
+                    float* q_out_dev, int32_t* tok_out_dev, void* stream);
+
+/* Acceptance on caller-provided rows (device): p_logits [n_rows][vocab] fp32 logits of the
+ * target, q_rows [n_test][vocab] distributions, x_dev[n_test] draft tokens, r_host[n_test].
+ * If n_rows == n_test + 1 and all are accepted a bonus token is drawn from the last row.
+ * result_host[0] = n_accepted, result_host[1] = corrected/bonus token (or -1). Synchronous. */
+int spec_accept_rows(const float* p_logits_dev, int n_rows, const float* q_rows_dev, const int32_t* x_dev,
+                     int n_test, int vocab, float temperature, float logit_scale, const float* r_host,
+                     float u_resample, int32_t* result_host, void* stream);
+
+/* Run-time switches: bit 0 = record HIP events around every projection launch of the
+ * target forward (read with spec_profile_read). */
+int spec_set_profile(spec_ctx* ctx, int flags);
+/* Sum of the recorded projection-kernel durations (ms) and launch count since the last read. */
+int spec_profile_read(spec_ctx* ctx, double* ms_total, long long* n_launches, double* bytes_total);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPEC_H */

@@ -40,12 +40,27 @@ from . import sampling
 PRE, POST = "pre-verify", "post-verify"
 
 
-def _decide(force, t, i, p_row, q_row, x, r):
+def _decide(force, t, i, p_row, q_row, x, r, margins=None):
     if force is not None:
         f = force(t, i)
         if f is not None:
             return bool(f)
+    if margins is not None:
+        margins.append(sampling.accept_margin(p_row, q_row, x, r))
     return sampling.accept(p_row, q_row, x, r)
+
+
+def _draw(weights, u, margins=None):
+    if margins is not None:
+        margins.append(sampling.sample_margin(weights, u))
+    return sampling.sample(weights, u)
+
+
+def _redraw(p_row, q_row, u, margins=None):
+    if margins is not None:
+        res = sampling.residual(p_row, q_row)
+        margins.append(sampling.sample_margin(res if res.sum() > 0.0 else p_row, u))
+    return sampling.resample(p_row, q_row, u)
 
 
 def _prefill(models, prompt):
@@ -60,10 +75,11 @@ def autoregressive(target, prompt, n_generate, uni, temperature=1.0, logit_scale
     committed = [int(t) for t in prompt]
     _prefill([target], committed)
     for t in range(n_generate):
+        mg = [] if trace is not None else None
         p = sampling.probs(target.feed([committed[-1]])[0], temperature, logit_scale)
-        committed.append(sampling.sample(p, uni.resample[t]))
+        committed.append(_draw(p, uni.resample[t], mg))
         if trace is not None:
-            trace.append({"mode": "ar", "n_accepted": 0, "n_committed": 1})
+            trace.append({"mode": "ar", "n_accepted": 0, "n_committed": 1, "margin": min(mg)})
     return committed[len(prompt):]
 
 
@@ -76,30 +92,32 @@ def speculative(target, draft, prompt, n_generate, gamma, uni, temperature=1.0, 
     t = 0
     while len(committed) - n0 < n_generate:
         frontier = committed[-1]
+        mg = [] if trace is not None else None
         inp = committed[draft.len:]           # the frontier, preceded by the last draft after an all-accept
         xs, qs = [], []
         for i in range(gamma):                # drafting phase: x_i ~ q_i
             q = P(draft.feed(inp)[-1])
-            x = sampling.sample(q, uni.draft[t, i])
+            x = _draw(q, uni.draft[t, i], mg)
             xs.append(x); qs.append(q)
             inp = [x]
         Pm = P(target.feed([frontier] + xs))  # p_1 .. p_{gamma+1}
         n_acc = 0
         for i in range(gamma):                # p_{i+1} (row i) tests x_{i+1}
-            if _decide(force, t, i, Pm[i], qs[i], xs[i], uni.accept[t, i]):
+            if _decide(force, t, i, Pm[i], qs[i], xs[i], uni.accept[t, i], mg):
                 n_acc += 1
             else:
                 break
         if n_acc == gamma:
-            y = sampling.sample(Pm[gamma], uni.resample[t])
+            y = _draw(Pm[gamma], uni.resample[t], mg)
         else:
-            y = sampling.resample(Pm[n_acc], qs[n_acc], uni.resample[t])
+            y = _redraw(Pm[n_acc], qs[n_acc], uni.resample[t], mg)
         committed += xs[:n_acc] + [y]
         keep = len(committed) - 1
         target.rollback(min(target.len, keep))
         draft.rollback(min(draft.len, keep))
         if trace is not None:
-            trace.append({"mode": "sd", "n_accepted": n_acc, "n_committed": n_acc + 1})
+            trace.append({"mode": "sd", "n_accepted": n_acc, "n_committed": n_acc + 1, "margin": min(mg),
+                          "tokens": xs[:n_acc] + [y]})
         t += 1
     return committed[n0:n0 + n_generate]
 
@@ -115,22 +133,24 @@ def pearl(target, draft, prompt, n_generate, gamma, uni, temperature=1.0, logit_
     t = 0
     while len(committed) - n0 < n_generate:
         frontier = committed[-1]
+        mg = [] if trace is not None else None
+        n_before = len(committed)
         if mode == PRE:
             base = draft.len
             xs, qs = [], []
             inp = frontier
             for i in range(gamma):            # q_i = M_q(x + [x_1..x_{i-1}]), x_i ~ q_i
                 q = P(draft.feed([inp])[0])
-                x = sampling.sample(q, uni.draft[t, i])
+                x = _draw(q, uni.draft[t, i], mg)
                 xs.append(x); qs.append(q)
                 inp = x
             p = P(target.feed([frontier])[0])  # p = M_p(x), side by side with the drafting
-            if _decide(force, t, 0, p, qs[0], xs[0], uni.accept[t, 0]):
+            if _decide(force, t, 0, p, qs[0], xs[0], uni.accept[t, 0], mg):
                 committed.append(xs[0])
                 pending, pending_q = xs[1:], qs[1:]
                 n_acc, n_com, mode_next = 1, 1, POST
             else:
-                committed.append(sampling.resample(p, qs[0], uni.resample[t]))
+                committed.append(_redraw(p, qs[0], uni.resample[t], mg))
                 draft.rollback(base + 1)      # keep the old frontier only
                 pending, pending_q = [], []
                 n_acc, n_com, mode_next = 0, 1, PRE
@@ -140,13 +160,13 @@ def pearl(target, draft, prompt, n_generate, gamma, uni, temperature=1.0, logit_
             inp = x[-1]
             for i in range(gamma):            # keep drafting x_{gamma+1}..x_{2 gamma}
                 q = P(draft.feed([inp])[0])
-                xn = sampling.sample(q, uni.draft[t, i])
+                xn = _draw(q, uni.draft[t, i], mg)
                 x.append(xn); qs.append(q)
                 inp = xn
             Pm = P(target.feed(x[:gamma]))    # P_i = M_p(x + [x_1..x_i]), i = 1..gamma
             n_acc = 0
             for i in range(1, gamma + 1):     # P_i tests x_{i+1} against q_{i+1}
-                if _decide(force, t, i - 1, Pm[i - 1], qs[i], x[i], uni.accept[t, i - 1]):
+                if _decide(force, t, i - 1, Pm[i - 1], qs[i], x[i], uni.accept[t, i - 1], mg):
                     n_acc += 1
                 else:
                     break
@@ -156,7 +176,7 @@ def pearl(target, draft, prompt, n_generate, gamma, uni, temperature=1.0, logit_
                 n_com, mode_next = gamma, POST
             else:
                 j = n_acc + 1                 # P_j rejected x_{j+1}
-                y = sampling.resample(Pm[j - 1], qs[j], uni.resample[t])
+                y = _redraw(Pm[j - 1], qs[j], uni.resample[t], mg)
                 committed += x[1:j] + [y]
                 keep = len(committed) - 1
                 target.rollback(keep)
@@ -164,7 +184,8 @@ def pearl(target, draft, prompt, n_generate, gamma, uni, temperature=1.0, logit_
                 pending, pending_q = [], []
                 n_com, mode_next = n_acc + 1, PRE
         if trace is not None:
-            trace.append({"mode": mode, "n_accepted": n_acc, "n_committed": n_com, "next_mode": mode_next})
+            trace.append({"mode": mode, "n_accepted": n_acc, "n_committed": n_com, "next_mode": mode_next,
+                          "margin": min(mg), "tokens": committed[n_before:]})
         mode = mode_next
         t += 1
     return committed[n0:n0 + n_generate]

@@ -59,3 +59,16 @@ def resample(p_row, q_row, u: float) -> int:
     if res.sum() > 0.0:
         return sample(res, u)
     return sample(p_row, u)
+
+
+def sample_margin(weights, u: float) -> float:
+    """How far u is from flipping an inverse-CDF draw: distance of u*total to the nearest CDF edge, over total."""
+    cdf = np.cumsum(np.asarray(weights, dtype=np.float64))
+    return float(np.min(np.abs(cdf / cdf[-1] - np.float64(u))))
+
+
+def accept_margin(p_row, q_row, x: int, r: float) -> float:
+    """How far an acceptance test is from flipping: |r q[x] - p[x]| / max(r q[x], p[x])."""
+    lhs, rhs = np.float64(r) * np.float64(q_row[x]), np.float64(p_row[x])
+    top = max(lhs, rhs)
+    return float(abs(lhs - rhs) / top) if top > 0 else 1.0

@@ -1,0 +1,210 @@
+// Skinny projection kernels for gfx950: y[M][N] = x[M][K] W^T with M <= 32 new tokens.
+//
+// Every weight is read exactly once per forward, so the kernel is HBM-bound (M flop per weight
+// byte pair); the MFMA unit is only the cheapest way to apply up to 32 activations to each
+// streamed weight.  W is stored panel-packed: a panel is 16 output rows, cut into 32-wide
+// K steps, and the 16x32 block of one step is laid out exactly as the A operand of
+// v_mfma_f32_16x16x32_bf16 (lane l = 16*(k/8) + row holds 8 consecutive k), 1 KiB per step.
+// A wave therefore reads its share of a panel as consecutive fully-coalesced 1 KiB loads.
+//
+// Work split: the K axis is cut into S slices; a workgroup of 8 waves owns one slice and a
+// contiguous range of panels; wave w owns `spw` consecutive steps of the slice and keeps the
+// matching activation fragments (the B operand) in registers for the whole kernel.  After every
+// round of 4 panels the 8 wave-partials are summed through LDS in a fixed order and written to
+// P[s][m][n] (fp32).  Consumers add the S slices in ascending order, so results do not depend
+// on timing.
+#include "spec_internal.h"
+
+#define GEMM_WAVES 8
+#define GEMM_THREADS (GEMM_WAVES * 64)
+#define GEMM_RP 4   // panels per reduction round
+
+GemmPlan gemm_plan(int M, int N, int K) {
+  GemmPlan p;
+  p.M = M; p.N = N; p.K = K;
+  p.steps = (K + 31) / 32;
+  p.NT = N / 16;
+  p.MT = M > 16 ? 2 : 1;
+  const int spwmax = p.MT == 1 ? 16 : 8;
+  p.S = (p.steps + GEMM_WAVES * spwmax - 1) / (GEMM_WAVES * spwmax);
+  // small matrices: cut K finer until every compute unit has a workgroup
+  while (p.S * p.NT < SPEC_NUM_CU && (p.steps + GEMM_WAVES * p.S * 2 - 1) / (GEMM_WAVES * p.S * 2) >= 2) p.S *= 2;
+  p.spw = (p.steps + GEMM_WAVES * p.S - 1) / (GEMM_WAVES * p.S);
+  p.Gs = SPEC_NUM_CU / p.S;
+  if (p.Gs < 1) p.Gs = 1;
+  if (p.Gs > p.NT) p.Gs = p.NT;
+  return p;
+}
+
+// Loads / multiplies one chunk of 8 K-steps (steps CH*8 .. CH*8+7 of the wave's range) of one panel.
+__device__ __forceinline__ void load_chunk(u32x4 (&a)[8], const u32x4* __restrict__ wp, int first, int nst) {
+#pragma unroll
+  for (int j = 0; j < 8; ++j)
+    if (first + j < nst) a[j] = __builtin_nontemporal_load(wp + (size_t)(first + j) * 64);
+}
+
+template <int MT, int SPWMAX, int CH>
+__device__ __forceinline__ void mma_chunk(f32x4 (&acc)[MT], const u32x4 (&a)[8], const bf16x8 (&b)[MT][SPWMAX],
+                                          int nst) {
+#pragma unroll
+  for (int j = 0; j < 8; ++j)
+    if (CH * 8 + j < nst) {
+      bf16x8 av = __builtin_bit_cast(bf16x8, a[j]);
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+        acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, b[mt][CH * 8 + j], acc[mt], 0, 0, 0);
+    }
+}
+
+template <int MT, int SPWMAX>
+__global__ __launch_bounds__(GEMM_THREADS) void gemm_partial_kernel(const bf16* __restrict__ X,
+                                                                    const u32x4* __restrict__ Wp,
+                                                                    float* __restrict__ P, int M, int N, int K,
+                                                                    int NT, int steps, int S, int spw, int Gs) {
+  constexpr int NCH = SPWMAX / 8;            // chunks per panel
+  constexpr int UNITS = GEMM_RP * NCH;       // chunks per reduction round (even)
+  __shared__ f32x4 red[GEMM_WAVES][GEMM_RP][MT][64];
+  const int s = blockIdx.x % S;
+  const int idx = blockIdx.x / S;
+  const int p0 = (int)((long long)idx * NT / Gs);
+  const int p1 = (int)((long long)(idx + 1) * NT / Gs);
+  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int c = lane & 15, kb = lane >> 4;
+  const int step0 = (s * GEMM_WAVES + w) * spw;
+  int nst = steps - step0;
+  if (nst > spw) nst = spw;
+  if (nst < 0) nst = 0;
+
+  // activation fragments of this wave's K range, kept for the whole kernel
+  bf16x8 b[MT][SPWMAX];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int j = 0; j < SPWMAX; ++j) {
+      const int m = mt * 16 + c;
+      const int k = (step0 + j) * 32 + kb * 8;
+      u32x4 v = {0u, 0u, 0u, 0u};
+      if (j < nst && m < M && k < K) v = *reinterpret_cast<const u32x4*>(X + (size_t)m * K + k);
+      b[mt][j] = __builtin_bit_cast(bf16x8, v);
+    }
+
+  const u32x4* wbase = Wp + (size_t)step0 * 64 + lane;
+  const size_t pstride = (size_t)steps * 64;   // 16-byte units per panel
+  u32x4 a[2][8];
+  if (p0 < p1) load_chunk(a[0], wbase + (size_t)p0 * pstride, 0, nst);
+
+  for (int pr = p0; pr < p1; pr += GEMM_RP) {
+    f32x4 acc[GEMM_RP][MT];
+#pragma unroll
+    for (int rp = 0; rp < GEMM_RP; ++rp)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) acc[rp][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    // software pipeline over the round's chunks: the loads of chunk u+1 (the first chunk of the
+    // next round included) are issued before the MFMAs of chunk u
+#pragma unroll
+    for (int u = 0; u < UNITS; ++u) {
+      const int pn = pr + (u + 1) / NCH;
+      if (pn < p1) load_chunk(a[(u + 1) & 1], wbase + (size_t)pn * pstride, ((u + 1) % NCH) * 8, nst);
+      if (pr + u / NCH < p1) {
+        if (u % NCH == 0) mma_chunk<MT, SPWMAX, 0>(acc[u / NCH], a[u & 1], b, nst);
+        else mma_chunk<MT, SPWMAX, (NCH > 1 ? 1 : 0)>(acc[u / NCH], a[u & 1], b, nst);
+      }
+    }
+
+#pragma unroll
+    for (int rp = 0; rp < GEMM_RP; ++rp)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) red[w][rp][mt][lane] = acc[rp][mt];
+    __syncthreads();
+    for (int item = threadIdx.x; item < GEMM_RP * MT * 64; item += GEMM_THREADS) {
+      const int l2 = item & 63, mt = (item >> 6) % MT, rp = item / (64 * MT);
+      const int p = pr + rp;
+      const int m = mt * 16 + (l2 & 15);
+      if (p < p1 && m < M) {
+        f32x4 t = red[0][rp][mt][l2];
+#pragma unroll
+        for (int ww = 1; ww < GEMM_WAVES; ++ww) t += red[ww][rp][mt][l2];
+        *reinterpret_cast<f32x4*>(P + ((size_t)s * M + m) * N + (size_t)p * 16 + (l2 >> 4) * 4) = t;
+      }
+    }
+    __syncthreads();
+  }
+}
+
+hipError_t launch_gemm_partials(const GemmPlan& p, const bf16* x, const void* wp, float* partials, hipStream_t st) {
+  dim3 grid(p.Gs * p.S), block(GEMM_THREADS);
+  if (p.MT == 1)
+    gemm_partial_kernel<1, 16><<<grid, block, 0, st>>>(x, (const u32x4*)wp, partials, p.M, p.N, p.K, p.NT, p.steps,
+                                                        p.S, p.spw, p.Gs);
+  else
+    gemm_partial_kernel<2, 8><<<grid, block, 0, st>>>(x, (const u32x4*)wp, partials, p.M, p.N, p.K, p.NT, p.steps,
+                                                       p.S, p.spw, p.Gs);
+  return hipGetLastError();
+}
+
+// y[i] = sum_s partials[s][i], slices added in ascending order
+__global__ void reduce_partials_kernel(float* __restrict__ y, const float* __restrict__ P, int S, size_t n4) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n4) return;
+  const f32x4* p = reinterpret_cast<const f32x4*>(P);
+  f32x4 t = p[i];
+  for (int s = 1; s < S; ++s) t += p[(size_t)s * n4 + i];
+  reinterpret_cast<f32x4*>(y)[i] = t;
+}
+
+hipError_t launch_reduce_partials(float* y, const float* partials, int S, size_t n, hipStream_t st) {
+  size_t n4 = n / 4;   // n = M*N with N % 16 == 0
+  reduce_partials_kernel<<<dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, st>>>(y, partials, S, n4);
+  return hipGetLastError();
+}
+
+// dst block (panel, step) lane l=(kb*16+r): W[16*panel + r][32*step + 8*kb .. +7]
+__global__ void pack_weight_kernel(u32x4* __restrict__ dst, const bf16* __restrict__ src, int N, int K, int steps,
+                                   int panel_start, int panel_step) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;   // 16-byte chunk index within this matrix
+  size_t total = (size_t)(N / 16) * steps * 64;
+  if (i >= total) return;
+  const int lane = (int)(i & 63);
+  const size_t blk = i >> 6;
+  const int step = (int)(blk % steps);
+  const int panel = (int)(blk / steps);
+  const int r = lane & 15, kb = lane >> 4;
+  const int k = step * 32 + kb * 8;
+  u32x4 v = {0u, 0u, 0u, 0u};
+  if (k < K) v = *reinterpret_cast<const u32x4*>(src + (size_t)(panel * 16 + r) * K + k);
+  const size_t dpanel = (size_t)panel_start + (size_t)panel * panel_step;
+  dst[(dpanel * steps + step) * 64 + lane] = v;
+}
+
+hipError_t launch_pack_weight(void* dst, const void* src, int N, int K, int panel_start, int panel_step,
+                              hipStream_t st) {
+  const int steps = (K + 31) / 32;
+  size_t total = (size_t)(N / 16) * steps * 64;
+  pack_weight_kernel<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st>>>((u32x4*)dst, (const bf16*)src, N, K,
+                                                                                  steps, panel_start, panel_step);
+  return hipGetLastError();
+}
+
+// Streaming-read probe: every workgroup sums a contiguous share with 16-byte loads.
+__global__ __launch_bounds__(512) void read_probe_kernel(const u32x4* __restrict__ src, size_t n16, unsigned* out) {
+  const size_t per = (n16 + gridDim.x - 1) / gridDim.x;
+  size_t b = (size_t)blockIdx.x * per, e = b + per;
+  if (e > n16) e = n16;
+  unsigned acc = 0;
+  size_t i = b + threadIdx.x;
+  for (; i + 3 * 512 < e; i += 4 * 512) {
+    u32x4 v0 = __builtin_nontemporal_load(src + i), v1 = __builtin_nontemporal_load(src + i + 512);
+    u32x4 v2 = __builtin_nontemporal_load(src + i + 1024), v3 = __builtin_nontemporal_load(src + i + 1536);
+    acc += v0.x ^ v0.y ^ v0.z ^ v0.w ^ v1.x ^ v1.y ^ v1.z ^ v1.w ^ v2.x ^ v2.y ^ v2.z ^ v2.w ^ v3.x ^ v3.y ^ v3.z ^ v3.w;
+  }
+  for (; i < e; i += 512) {
+    u32x4 v = __builtin_nontemporal_load(src + i);
+    acc += v.x ^ v.y ^ v.z ^ v.w;
+  }
+  if (acc == 0x9E3779B9u) out[0] = acc;   // practically never: keeps the loads alive without a store per thread
+}
+
+hipError_t launch_read_probe(const void* src, size_t bytes, void* out, hipStream_t st) {
+  read_probe_kernel<<<dim3(SPEC_NUM_CU * 4), dim3(512), 0, st>>>((const u32x4*)src, bytes / 16, (unsigned*)out);
+  return hipGetLastError();
+}

@@ -1,0 +1,161 @@
+// Small per-token kernels between the projections (gfx950): token gather, embedding,
+// residual add + RMSNorm, RoPE + KV append, SiLU*mul.  All of them read the fp32 K-slice
+// partials of the preceding projection and add the slices in ascending order.
+#include "spec_internal.h"
+
+__global__ void gather_tokens_kernel(int* tok_out, const int* ring, TokenSrc src) {
+  int i = threadIdx.x;
+  if (i < src.n) tok_out[i] = src.imm[i] >= 0 ? src.imm[i] : ring[src.slot[i]];
+}
+hipError_t launch_gather_tokens(int* tok_out, const int* ring, TokenSrc src, hipStream_t st) {
+  gather_tokens_kernel<<<1, 64, 0, st>>>(tok_out, ring, src);
+  return hipGetLastError();
+}
+
+__global__ void set_int_kernel(int* dst, int v) { dst[0] = v; }
+__global__ void add_int_kernel(int* dst, int d) { dst[0] += d; }
+hipError_t launch_set_int(int* dst, int value, hipStream_t st) {
+  set_int_kernel<<<1, 1, 0, st>>>(dst, value);
+  return hipGetLastError();
+}
+hipError_t launch_add_int(int* dst, int delta, hipStream_t st) {
+  add_int_kernel<<<1, 1, 0, st>>>(dst, delta);
+  return hipGetLastError();
+}
+__global__ void set_pages_kernel(int* bt, PageUpdate u) {
+  int i = threadIdx.x;
+  if (i < u.count) bt[u.first + i] = u.page[i];
+}
+hipError_t launch_set_pages(int* block_table, PageUpdate u, hipStream_t st) {
+  set_pages_kernel<<<1, 64, 0, st>>>(block_table, u);
+  return hipGetLastError();
+}
+
+// h[m][:] = float(E[tok[m]][:]); an id outside the vocabulary reads row 0 (ids are validated on the host)
+__global__ void embed_kernel(float* __restrict__ h, const bf16* __restrict__ E, const int* __restrict__ tok, int d,
+                             int vocab) {
+  const int m = blockIdx.x;
+  int t = tok[m];
+  if (t < 0 || t >= vocab) t = 0;
+  const bf16* row = E + (size_t)t * d;
+  for (int i = threadIdx.x; i < d; i += blockDim.x) h[(size_t)m * d + i] = __bfloat162float(row[i]);
+}
+hipError_t launch_embed(float* h, const bf16* embed, const int* tok, int M, int d, int vocab, hipStream_t st) {
+  embed_kernel<<<M, 256, 0, st>>>(h, embed, tok, d, vocab);
+  return hipGetLastError();
+}
+
+__device__ __forceinline__ float block_sum(float v, float* sh) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  const int w = threadIdx.x >> 6;
+  if ((threadIdx.x & 63) == 0) sh[w] = v;
+  __syncthreads();
+  float t = 0.f;
+  const int nw = blockDim.x >> 6;
+  for (int i = 0; i < nw; ++i) t += sh[i];
+  __syncthreads();
+  return t;
+}
+
+// h[m] += sum_s P[s][m] ; a[m] = h[m] * rsqrt(mean(h[m]^2) + eps) * gain      (one workgroup per row)
+__global__ __launch_bounds__(256) void addnorm_kernel(float* __restrict__ h, const float* __restrict__ P, int S,
+                                                      const bf16* __restrict__ gain, bf16* __restrict__ a, int M,
+                                                      int d, float eps) {
+  __shared__ float sh[4];
+  const int m = blockIdx.x;
+  float* hr = h + (size_t)m * d;
+  float ss = 0.f;
+  for (int i = threadIdx.x; i < d; i += 256) {
+    float v = hr[i];
+    if (P)
+      for (int s = 0; s < S; ++s) v += P[((size_t)s * M + m) * d + i];
+    hr[i] = v;
+    ss += v * v;
+  }
+  const float tot = block_sum(ss, sh);
+  const float inv = 1.0f / sqrtf(tot / (float)d + eps);
+  for (int i = threadIdx.x; i < d; i += 256)
+    a[(size_t)m * d + i] = __float2bfloat16(hr[i] * inv * __bfloat162float(gain[i]));
+}
+hipError_t launch_addnorm(float* h, const float* partials, int S, const bf16* gain, bf16* a, int M, int d, float eps,
+                          hipStream_t st) {
+  addnorm_kernel<<<M, 256, 0, st>>>(h, partials, S, gain, a, M, d, eps);
+  return hipGetLastError();
+}
+
+// One workgroup per (token, head) of the fused QKV output; thread e handles the pair (e, e + dh/2).
+// q heads: rotate, store bf16 [M][Hq][dh].  k heads: rotate, store into the page in K-operand order.
+// v heads: store into the page in V-operand order.  Position of token i is len + i.
+__global__ void rope_append_kernel(const float* __restrict__ P, int S, bf16* __restrict__ q, bf16* __restrict__ pool,
+                                   const int* __restrict__ block_table, const int* __restrict__ len_ptr, KvGeom g,
+                                   int layer, int M, int Hq, float theta) {
+  const int i = blockIdx.x, head = blockIdx.y;
+  const int dh = g.head_dim, half = dh >> 1, Hkv = g.n_kv_heads;
+  const int N = (Hq + 2 * Hkv) * dh;
+  const int e = threadIdx.x;
+  if (e >= half) return;
+  const int pos = len_ptr[0] + i;
+  float x0 = 0.f, x1 = 0.f;
+  for (int s = 0; s < S; ++s) {
+    const float* row = P + ((size_t)s * M + i) * N + (size_t)head * dh;
+    x0 += row[e];
+    x1 += row[e + half];
+  }
+  if (head < Hq + Hkv) {   // rotate pair (e, e + dh/2) by pos * theta^(-2e/dh)
+    const double ang = (double)pos * pow((double)theta, -2.0 * (double)e / (double)dh);
+    const float cs = (float)cos(ang), sn = (float)sin(ang);
+    const float y0 = x0 * cs - x1 * sn, y1 = x0 * sn + x1 * cs;
+    x0 = y0; x1 = y1;
+  }
+  if (head < Hq) {
+    bf16* dst = q + ((size_t)i * Hq + head) * dh;
+    dst[e] = __float2bfloat16(x0);
+    dst[e + half] = __float2bfloat16(x1);
+    return;
+  }
+  const int page = block_table[pos / SPEC_PAGE_TOKENS];
+  const int r = pos % SPEC_PAGE_TOKENS;
+  if (head < Hq + Hkv) {
+    bf16* blk = pool + g.offset(page, layer, 0, head - Hq);
+    const int tile = r >> 4, rr = r & 15, nsteps = dh >> 5;
+    for (int t = 0; t < 2; ++t) {
+      const int ee = t ? e + half : e;
+      const size_t off = ((size_t)((tile * nsteps + (ee >> 5)) * 64 + ((ee & 31) >> 3) * 16 + rr)) * 8 + (ee & 7);
+      blk[off] = __float2bfloat16(t ? x1 : x0);
+    }
+  } else {
+    bf16* blk = pool + g.offset(page, layer, 1, head - Hq - Hkv);
+    const int chunk = r >> 5, r32 = r & 31;
+    const int slot = ((r32 & 15) >> 2) * 8 + (r32 >> 4) * 4 + (r32 & 3);
+    blk[((size_t)chunk * dh + e) * 32 + slot] = __float2bfloat16(x0);
+    blk[((size_t)chunk * dh + e + half) * 32 + slot] = __float2bfloat16(x1);
+  }
+}
+hipError_t launch_rope_append(const float* partials, int S, bf16* q, bf16* pool, const int* block_table,
+                              const int* len_ptr, KvGeom g, int layer, int M, int Hq, float theta, hipStream_t st) {
+  dim3 grid(M, Hq + 2 * g.n_kv_heads), block(64);
+  rope_append_kernel<<<grid, block, 0, st>>>(partials, S, q, pool, block_table, len_ptr, g, layer, M, Hq, theta);
+  return hipGetLastError();
+}
+
+// z[m][f] = silu(gate) * up, gate/up panels interleaved in the fused projection output (width 2F)
+__global__ void silu_mul_kernel(const float* __restrict__ P, int S, bf16* __restrict__ z, int M, int F) {
+  const int m = blockIdx.y;
+  const int f = blockIdx.x * blockDim.x + threadIdx.x;
+  if (f >= F) return;
+  const int gc = (f >> 4) * 32 + (f & 15);
+  float gv = 0.f, uv = 0.f;
+  for (int s = 0; s < S; ++s) {
+    const float* row = P + ((size_t)s * M + m) * (2 * (size_t)F);
+    gv += row[gc];
+    uv += row[gc + 16];
+  }
+  const float sg = gv / (1.0f + __expf(-gv));
+  z[(size_t)m * F + f] = __float2bfloat16(sg * uv);
+}
+hipError_t launch_silu_mul(const float* partials, int S, bf16* z, int M, int F, hipStream_t st) {
+  dim3 grid((F + 255) / 256, M), block(256);
+  silu_mul_kernel<<<grid, block, 0, st>>>(partials, S, z, M, F);
+  return hipGetLastError();
+}

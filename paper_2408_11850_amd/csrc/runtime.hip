@@ -1,0 +1,765 @@
+// Host runtime of the speculative-decoding library: contexts, the paged KV allocator, the
+// forward pass as a chain of kernel launches, the draft-token ring with its q-row cache, the
+// accept step's bookkeeping and the three decoding loops (paper Section 2 and Algorithms 1, 2).
+#include <chrono>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "spec_internal.h"
+
+static thread_local char g_err[512] = "";
+void spec_set_error(const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+}
+extern "C" const char* spec_last_error(void) { return g_err; }
+
+#define HIPCHK(expr)                                                                        \
+  do {                                                                                      \
+    hipError_t e_ = (expr);                                                                 \
+    if (e_ != hipSuccess) {                                                                 \
+      spec_set_error("%s failed: %s (%s:%d)", #expr, hipGetErrorString(e_), __FILE__, __LINE__); \
+      return SPEC_E_HIP;                                                                    \
+    }                                                                                       \
+  } while (0)
+#define FAIL(code, ...)        \
+  do {                         \
+    spec_set_error(__VA_ARGS__); \
+    return (code);             \
+  } while (0)
+
+namespace {
+
+struct ModelRt {
+  spec_model_desc d;
+  const void *tok_embed = nullptr, *final_norm = nullptr, *lm_head = nullptr;
+  std::vector<const void*> attn_norm, wqkv, wo, ffn_norm, wgu, wdown;
+  hipStream_t stream = nullptr;
+  KvGeom geom;
+  bf16* pool = nullptr;
+  int n_pages = 0;
+  int* block_table_dev = nullptr;
+  std::vector<int> block_table;   // pages of the sequence, in order
+  std::vector<int> free_pages;
+  int len = 0;                    // host mirror of *len_dev
+  int* len_dev = nullptr;
+  int* tok_in = nullptr;
+  float* h = nullptr;
+  bf16 *a = nullptr, *qbuf = nullptr, *attn_out = nullptr, *z = nullptr;
+  float *partials = nullptr, *opart = nullptr, *mlpart = nullptr, *logits = nullptr;
+  long long n_forwards = 0;
+};
+
+struct ProfEvents {
+  std::vector<hipEvent_t> ev;     // pairs
+  size_t used = 0;
+  double bytes = 0.0;
+};
+
+}  // namespace
+
+struct spec_ctx {
+  spec_config cfg;
+  ModelRt m[2];
+  int ring_n = 0;
+  float* qcache = nullptr;        // [ring_n][vocab]
+  int* ring = nullptr;            // [SPEC_RING_MAX] draft tokens
+  hipEvent_t ev_slot[SPEC_RING_MAX];
+  bool ev_slot_valid[SPEC_RING_MAX];
+  float* accept_scratch = nullptr;
+  AcceptResult* res_dev = nullptr;
+  AcceptResult* res_host = nullptr;
+  std::vector<int> committed;
+  int n_prompt = 0;
+  int ring_base = 0, n_drafted = 0;
+  bool first_verified = false;    // x_1 of the ring is already committed (it is the frontier)
+  int last_verify_rows = 0;
+  bool prefilled = false;
+  int profile_flags = 0;
+  ProfEvents prof;
+};
+
+namespace {
+
+inline int slot_of(const spec_ctx* c, int i /* 1-based draft index */) { return (c->ring_base + i - 1) % c->ring_n; }
+
+int check_desc(const spec_model_desc& d, const char* name) {
+  if (d.n_layers < 1 || d.d_model < 32 || d.n_heads < 1 || d.n_kv_heads < 1 || d.d_ffn < 16 || d.vocab < 16)
+    FAIL(SPEC_E_INVAL, "%s: non-positive model dimension", name);
+  if (d.head_dim != 64 && d.head_dim != 128) FAIL(SPEC_E_INVAL, "%s: head_dim must be 64 or 128", name);
+  if (d.n_heads % d.n_kv_heads) FAIL(SPEC_E_INVAL, "%s: n_heads must be a multiple of n_kv_heads", name);
+  if (d.d_model % 16 || d.d_ffn % 16 || d.vocab % 16) FAIL(SPEC_E_INVAL, "%s: d_model, d_ffn, vocab must be multiples of 16", name);
+  if (!(d.rope_theta > 1.0f) || !(d.rms_eps >= 0.0f)) FAIL(SPEC_E_INVAL, "%s: bad rope_theta / rms_eps", name);
+  return SPEC_OK;
+}
+
+template <typename T>
+int dev_alloc(T** p, size_t count) {
+  void* v = nullptr;
+  hipError_t e = hipMalloc(&v, count * sizeof(T) + 256);
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    FAIL(SPEC_E_NOMEM, "hipMalloc of %zu bytes failed: %s", count * sizeof(T), hipGetErrorString(e));
+  }
+  *p = (T*)v;
+  return SPEC_OK;
+}
+
+int init_model(ModelRt& m, const spec_model_desc& d, const spec_weights& w, const spec_config& cfg, hipStream_t st) {
+  m.d = d;
+  m.stream = st;
+  m.tok_embed = w.tok_embed; m.final_norm = w.final_norm; m.lm_head = w.lm_head;
+  if (!w.tok_embed || !w.final_norm || !w.lm_head || !w.attn_norm || !w.wqkv || !w.wo || !w.ffn_norm || !w.w_gateup ||
+      !w.w_down)
+    FAIL(SPEC_E_INVAL, "null weight pointer");
+  for (int l = 0; l < d.n_layers; ++l) {
+    if (!w.attn_norm[l] || !w.wqkv[l] || !w.wo[l] || !w.ffn_norm[l] || !w.w_gateup[l] || !w.w_down[l])
+      FAIL(SPEC_E_INVAL, "null weight pointer in layer %d", l);
+    m.attn_norm.push_back(w.attn_norm[l]); m.wqkv.push_back(w.wqkv[l]); m.wo.push_back(w.wo[l]);
+    m.ffn_norm.push_back(w.ffn_norm[l]); m.wgu.push_back(w.w_gateup[l]); m.wdown.push_back(w.w_down[l]);
+  }
+  m.geom.n_layers = d.n_layers; m.geom.n_kv_heads = d.n_kv_heads; m.geom.head_dim = d.head_dim;
+  m.n_pages = (cfg.max_seq + SPEC_PAGE_TOKENS - 1) / SPEC_PAGE_TOKENS + 1;
+  int rc;
+  const size_t pool_elems = (size_t)m.n_pages * m.geom.page_elems();
+  if ((rc = dev_alloc(&m.pool, pool_elems))) return rc;
+  // stale slots are read (then masked) by the attention kernel: they must hold finite numbers
+  HIPCHK(hipMemset(m.pool, 0, pool_elems * sizeof(bf16)));
+  if ((rc = dev_alloc(&m.block_table_dev, (size_t)m.n_pages))) return rc;
+  HIPCHK(hipMemset(m.block_table_dev, 0, m.n_pages * sizeof(int)));
+  if ((rc = dev_alloc(&m.len_dev, 4))) return rc;
+  HIPCHK(hipMemset(m.len_dev, 0, 16));
+  for (int p = m.n_pages - 1; p >= 0; --p) m.free_pages.push_back(p);
+  const int MX = SPEC_MAX_TOKENS;
+  const int qkvN = (d.n_heads + 2 * d.n_kv_heads) * d.head_dim;
+  const int kmax = d.d_model > d.d_ffn ? d.d_model : d.d_ffn;
+  const int amax = kmax > d.n_heads * d.head_dim ? kmax : d.n_heads * d.head_dim;
+  if ((rc = dev_alloc(&m.tok_in, (size_t)MX))) return rc;
+  if ((rc = dev_alloc(&m.h, (size_t)MX * d.d_model))) return rc;
+  if ((rc = dev_alloc(&m.a, (size_t)MX * amax))) return rc;
+  if ((rc = dev_alloc(&m.qbuf, (size_t)MX * d.n_heads * d.head_dim))) return rc;
+  if ((rc = dev_alloc(&m.attn_out, (size_t)MX * d.n_heads * d.head_dim))) return rc;
+  if ((rc = dev_alloc(&m.z, (size_t)MX * d.d_ffn))) return rc;
+  size_t pb = 0;
+  const int shapes[5][2] = {{qkvN, d.d_model}, {d.d_model, d.n_heads * d.head_dim}, {2 * d.d_ffn, d.d_model},
+                            {d.d_model, d.d_ffn}, {d.vocab, d.d_model}};
+  for (int mm : {1, 16, MX})
+    for (auto& s : shapes) {
+      size_t b = gemm_plan(mm, s[0], s[1]).partial_bytes();
+      if (b > pb) pb = b;
+    }
+  if ((rc = dev_alloc(&m.partials, pb / sizeof(float)))) return rc;
+  const size_t aw = attention_workspace_floats(d.n_heads, d.n_kv_heads, d.head_dim, m.n_pages * SPEC_PAGE_TOKENS);
+  if ((rc = dev_alloc(&m.opart, aw))) return rc;
+  m.mlpart = m.opart + (aw / (d.head_dim + 2)) * d.head_dim;
+  if ((rc = dev_alloc(&m.logits, (size_t)MX * d.vocab))) return rc;
+  return SPEC_OK;
+}
+
+void free_model(ModelRt& m) {
+  void* ptrs[] = {m.pool, m.block_table_dev, m.len_dev, m.tok_in, m.h, m.a, m.qbuf, m.attn_out, m.z, m.partials,
+                  m.opart, m.logits};
+  for (void* p : ptrs)
+    if (p) (void)hipFree(p);
+}
+
+// make sure pages exist for positions [0, new_len)
+int ensure_pages(ModelRt& m, int new_len) {
+  const int need = (new_len + SPEC_PAGE_TOKENS - 1) / SPEC_PAGE_TOKENS;
+  const int have = (int)m.block_table.size();
+  if (need <= have) return SPEC_OK;
+  if ((size_t)(need - have) > m.free_pages.size())
+    FAIL(SPEC_E_NOMEM, "KV cache full: %d tokens need %d pages, %d in use, %zu free", new_len, need, have,
+         m.free_pages.size());
+  int first = have;
+  while ((int)m.block_table.size() < need) {
+    PageUpdate u;
+    u.first = (int)m.block_table.size();
+    u.count = 0;
+    while (u.count < 8 && (int)m.block_table.size() < need) {
+      const int pg = m.free_pages.back();
+      m.free_pages.pop_back();
+      m.block_table.push_back(pg);
+      u.page[u.count++] = pg;
+    }
+    HIPCHK(launch_set_pages(m.block_table_dev, u, m.stream));
+  }
+  (void)first;
+  return SPEC_OK;
+}
+
+int prof_begin(spec_ctx* c, hipStream_t st, double bytes) {
+  ProfEvents& p = c->prof;
+  if (p.used + 2 > p.ev.size()) {
+    for (int i = 0; i < 2; ++i) {
+      hipEvent_t e;
+      HIPCHK(hipEventCreate(&e));
+      p.ev.push_back(e);
+    }
+  }
+  HIPCHK(hipEventRecord(p.ev[p.used], st));
+  p.bytes += bytes;
+  return SPEC_OK;
+}
+int prof_end(spec_ctx* c, hipStream_t st) {
+  ProfEvents& p = c->prof;
+  HIPCHK(hipEventRecord(p.ev[p.used + 1], st));
+  p.used += 2;
+  return SPEC_OK;
+}
+
+int run_gemm(spec_ctx* c, int which, ModelRt& m, int M, int N, int K, const bf16* x, const void* w, GemmPlan* plan_out) {
+  GemmPlan p = gemm_plan(M, N, K);
+  const bool prof = (c->profile_flags & 1) && which == SPEC_TARGET;
+  int rc;
+  if (prof && (rc = prof_begin(c, m.stream, (double)p.weight_bytes()))) return rc;
+  HIPCHK(launch_gemm_partials(p, x, w, m.partials, m.stream));
+  if (prof && (rc = prof_end(c, m.stream))) return rc;
+  *plan_out = p;
+  return SPEC_OK;
+}
+
+// One forward of model `which` over M tokens.  logit_rows: 0 = none (prefill), 1 = last row only, M = all rows.
+int forward(spec_ctx* c, int which, const TokenSrc& src, int logit_rows) {
+  ModelRt& m = c->m[which];
+  const spec_model_desc& d = m.d;
+  const int M = src.n;
+  if (M < 1 || M > SPEC_MAX_TOKENS) FAIL(SPEC_E_INVAL, "forward over %d tokens (1..%d allowed)", M, SPEC_MAX_TOKENS);
+  int rc;
+  if ((rc = ensure_pages(m, m.len + M))) return rc;
+  hipStream_t st = m.stream;
+  HIPCHK(launch_gather_tokens(m.tok_in, c->ring, src, st));
+  HIPCHK(launch_embed(m.h, (const bf16*)m.tok_embed, m.tok_in, M, d.d_model, d.vocab, st));
+  const int qkvN = (d.n_heads + 2 * d.n_kv_heads) * d.head_dim;
+  const int HD = d.n_heads * d.head_dim;
+  GemmPlan p;
+  const float* prev = nullptr;
+  int prevS = 0;
+  for (int l = 0; l < d.n_layers; ++l) {
+    HIPCHK(launch_addnorm(m.h, prev, prevS, (const bf16*)m.attn_norm[l], m.a, M, d.d_model, d.rms_eps, st));
+    if ((rc = run_gemm(c, which, m, M, qkvN, d.d_model, m.a, m.wqkv[l], &p))) return rc;
+    HIPCHK(launch_rope_append(m.partials, p.S, m.qbuf, m.pool, m.block_table_dev, m.len_dev, m.geom, l, M, d.n_heads,
+                              d.rope_theta, st));
+    HIPCHK(launch_attention(m.qbuf, m.pool, m.block_table_dev, m.len_dev, m.geom, l, M, d.n_heads, m.len, m.opart,
+                            m.mlpart, m.attn_out, st));
+    if ((rc = run_gemm(c, which, m, M, d.d_model, HD, m.attn_out, m.wo[l], &p))) return rc;
+    HIPCHK(launch_addnorm(m.h, m.partials, p.S, (const bf16*)m.ffn_norm[l], m.a, M, d.d_model, d.rms_eps, st));
+    if ((rc = run_gemm(c, which, m, M, 2 * d.d_ffn, d.d_model, m.a, m.wgu[l], &p))) return rc;
+    HIPCHK(launch_silu_mul(m.partials, p.S, m.z, M, d.d_ffn, st));
+    if ((rc = run_gemm(c, which, m, M, d.d_model, d.d_ffn, m.z, m.wdown[l], &p))) return rc;
+    prev = m.partials;
+    prevS = p.S;
+  }
+  if (logit_rows > 0) {
+    HIPCHK(launch_addnorm(m.h, prev, prevS, (const bf16*)m.final_norm, m.a, M, d.d_model, d.rms_eps, st));
+    const int rows = logit_rows >= M ? M : 1;
+    const bf16* x = m.a + (size_t)(M - rows) * d.d_model;
+    if ((rc = run_gemm(c, which, m, rows, d.vocab, d.d_model, x, m.lm_head, &p))) return rc;
+    HIPCHK(launch_reduce_partials(m.logits, m.partials, p.S, (size_t)rows * d.vocab, st));
+  }
+  HIPCHK(launch_add_int(m.len_dev, M, st));
+  m.len += M;
+  m.n_forwards++;
+  return SPEC_OK;
+}
+
+void reset_ring(spec_ctx* c) {
+  c->ring_base = 0;
+  c->n_drafted = 0;
+  c->first_verified = false;
+}
+
+int rollback_model(spec_ctx* c, int which, int new_len) {
+  ModelRt& m = c->m[which];
+  if (new_len < 0 || new_len > m.len) FAIL(SPEC_E_INVAL, "rollback to %d outside [0, %d]", new_len, m.len);
+  if (new_len == m.len) return SPEC_OK;
+  m.len = new_len;
+  HIPCHK(launch_set_int(m.len_dev, new_len, m.stream));
+  const int keep = (new_len + SPEC_PAGE_TOKENS - 1) / SPEC_PAGE_TOKENS;
+  while ((int)m.block_table.size() > keep) {
+    m.free_pages.push_back(m.block_table.back());
+    m.block_table.pop_back();
+  }
+  return SPEC_OK;
+}
+
+}  // namespace
+
+// -------------------------------------------------------------------------------------------
+extern "C" int spec_init(const spec_config* cfg, const spec_model_desc* target, const spec_weights* tw,
+                         const spec_model_desc* draft, const spec_weights* dw, spec_ctx** out) {
+  if (!cfg || !target || !tw || !draft || !dw || !out) FAIL(SPEC_E_INVAL, "null argument");
+  *out = nullptr;
+  int rc;
+  if ((rc = check_desc(*target, "target")) || (rc = check_desc(*draft, "draft"))) return rc;
+  if (target->vocab != draft->vocab) FAIL(SPEC_E_INVAL, "target and draft vocabularies differ");
+  if (cfg->gamma_max < 1 || cfg->gamma_max > SPEC_MAX_TOKENS - 1) FAIL(SPEC_E_INVAL, "gamma_max outside 1..%d", SPEC_MAX_TOKENS - 1);
+  if (cfg->page_tokens != SPEC_PAGE_TOKENS) FAIL(SPEC_E_INVAL, "page_tokens must be %d", SPEC_PAGE_TOKENS);
+  if (cfg->max_seq < 1) FAIL(SPEC_E_INVAL, "max_seq must be positive");
+  if (!(cfg->temperature >= 0.0f) || !(cfg->logit_scale > 0.0f)) FAIL(SPEC_E_INVAL, "bad temperature / logit_scale");
+  spec_ctx* c = new (std::nothrow) spec_ctx();
+  if (!c) FAIL(SPEC_E_NOMEM, "out of host memory");
+  c->cfg = *cfg;
+  for (int i = 0; i < SPEC_RING_MAX; ++i) c->ev_slot_valid[i] = false, c->ev_slot[i] = nullptr;
+  c->ring_n = 2 * cfg->gamma_max;
+  if (c->ring_n > SPEC_RING_MAX) c->ring_n = SPEC_RING_MAX;
+  rc = init_model(c->m[SPEC_TARGET], *target, *tw, *cfg, (hipStream_t)cfg->stream_target);
+  if (!rc) rc = init_model(c->m[SPEC_DRAFT], *draft, *dw, *cfg, (hipStream_t)cfg->stream_draft);
+  if (!rc) rc = dev_alloc(&c->qcache, (size_t)c->ring_n * target->vocab);
+  if (!rc) rc = dev_alloc(&c->ring, (size_t)SPEC_RING_MAX);
+  if (!rc) rc = dev_alloc(&c->accept_scratch, (size_t)256 + target->vocab);
+  if (!rc) rc = dev_alloc(&c->res_dev, (size_t)1);
+  if (!rc) {
+    hipError_t e = hipMemset(c->ring, 0, SPEC_RING_MAX * sizeof(int));
+    if (e == hipSuccess) e = hipHostMalloc((void**)&c->res_host, sizeof(AcceptResult), hipHostMallocDefault);
+    for (int i = 0; i < c->ring_n && e == hipSuccess; ++i) e = hipEventCreateWithFlags(&c->ev_slot[i], hipEventDisableTiming);
+    if (e == hipSuccess) e = hipDeviceSynchronize();
+    if (e != hipSuccess) {
+      spec_set_error("context set-up failed: %s", hipGetErrorString(e));
+      rc = SPEC_E_HIP;
+    }
+  }
+  if (rc) {
+    spec_free(c);
+    return rc;
+  }
+  *out = c;
+  return SPEC_OK;
+}
+
+extern "C" void spec_free(spec_ctx* c) {
+  if (!c) return;
+  (void)hipDeviceSynchronize();
+  free_model(c->m[0]);
+  free_model(c->m[1]);
+  if (c->qcache) (void)hipFree(c->qcache);
+  if (c->ring) (void)hipFree(c->ring);
+  if (c->accept_scratch) (void)hipFree(c->accept_scratch);
+  if (c->res_dev) (void)hipFree(c->res_dev);
+  if (c->res_host) (void)hipHostFree(c->res_host);
+  for (int i = 0; i < SPEC_RING_MAX; ++i)
+    if (c->ev_slot[i]) (void)hipEventDestroy(c->ev_slot[i]);
+  for (hipEvent_t e : c->prof.ev) (void)hipEventDestroy(e);
+  delete c;
+}
+
+extern "C" int spec_prefill(spec_ctx* c, const int32_t* prompt, int n_prompt, int which_mask) {
+  if (!c || !prompt) FAIL(SPEC_E_INVAL, "null argument");
+  if (n_prompt < 1) FAIL(SPEC_E_INVAL, "the prompt must hold at least one token");
+  if (!(which_mask & 3)) FAIL(SPEC_E_INVAL, "which_mask selects no model");
+  const int V = c->m[0].d.vocab;
+  for (int i = 0; i < n_prompt; ++i)
+    if (prompt[i] < 0 || prompt[i] >= V) FAIL(SPEC_E_INVAL, "prompt[%d] = %d outside the vocabulary", i, prompt[i]);
+  for (int w = 0; w < 2; ++w)
+    if (n_prompt - 1 + 2 * c->cfg.gamma_max > c->m[w].n_pages * SPEC_PAGE_TOKENS)
+      FAIL(SPEC_E_NOMEM, "prompt of %d tokens does not fit max_seq", n_prompt);
+  int rc;
+  HIPCHK(hipStreamSynchronize(c->m[0].stream));
+  HIPCHK(hipStreamSynchronize(c->m[1].stream));
+  for (int w = 0; w < 2; ++w)
+    if ((rc = rollback_model(c, w, 0))) return rc;
+  reset_ring(c);
+  c->committed.assign(prompt, prompt + n_prompt);
+  c->n_prompt = n_prompt;
+  c->last_verify_rows = 0;
+  for (int w = 0; w < 2; ++w) {
+    if (!((which_mask >> w) & 1)) continue;
+    for (int s = 0; s < n_prompt - 1; s += SPEC_MAX_TOKENS) {
+      TokenSrc src;
+      src.n = (n_prompt - 1 - s) < SPEC_MAX_TOKENS ? (n_prompt - 1 - s) : SPEC_MAX_TOKENS;
+      for (int i = 0; i < src.n; ++i) src.imm[i] = prompt[s + i], src.slot[i] = 0;
+      if ((rc = forward(c, w, src, 0))) return rc;
+    }
+  }
+  HIPCHK(hipStreamSynchronize(c->m[0].stream));
+  HIPCHK(hipStreamSynchronize(c->m[1].stream));
+  c->prefilled = true;
+  return SPEC_OK;
+}
+
+extern "C" int spec_draft_step(spec_ctx* c, float u, int32_t* tok_out) {
+  if (!c) FAIL(SPEC_E_INVAL, "null context");
+  if (!c->prefilled) FAIL(SPEC_E_STATE, "spec_prefill has not run");
+  if (!(u >= 0.0f && u < 1.0f)) FAIL(SPEC_E_INVAL, "uniform outside [0,1)");
+  if (c->n_drafted >= c->ring_n) FAIL(SPEC_E_STATE, "%d unverified drafts already pending", c->n_drafted);
+  ModelRt& m = c->m[SPEC_DRAFT];
+  int rc;
+  TokenSrc src;
+  if (c->n_drafted == 0) {
+    // feed every committed token the draft cache lacks; the last one is the frontier
+    int missing = (int)c->committed.size() - m.len;
+    if (missing < 1) FAIL(SPEC_E_STATE, "draft cache holds %d tokens but only %zu are committed", m.len, c->committed.size());
+    while (missing > SPEC_MAX_TOKENS) {
+      src.n = SPEC_MAX_TOKENS;
+      for (int i = 0; i < src.n; ++i) src.imm[i] = c->committed[m.len + i], src.slot[i] = 0;
+      if ((rc = forward(c, SPEC_DRAFT, src, 0))) return rc;
+      missing -= SPEC_MAX_TOKENS;
+    }
+    src.n = missing;
+    const int base = m.len;
+    for (int i = 0; i < missing; ++i) src.imm[i] = c->committed[base + i], src.slot[i] = 0;
+  } else {
+    src.n = 1;
+    src.imm[0] = -1;
+    src.slot[0] = slot_of(c, c->n_drafted);
+  }
+  if ((rc = forward(c, SPEC_DRAFT, src, 1))) return rc;
+  const int slot = slot_of(c, c->n_drafted + 1);
+  const bool greedy = c->cfg.temperature == 0.0f;
+  const float mult = greedy ? 1.0f : c->cfg.logit_scale / c->cfg.temperature;
+  HIPCHK(launch_sample_row(m.logits, m.d.vocab, mult, greedy ? 1 : 0, u, c->qcache + (size_t)slot * m.d.vocab,
+                           c->ring + slot, m.stream));
+  HIPCHK(hipEventRecord(c->ev_slot[slot], m.stream));
+  c->ev_slot_valid[slot] = true;
+  c->n_drafted++;
+  if (tok_out) {
+    HIPCHK(hipStreamSynchronize(m.stream));
+    HIPCHK(hipMemcpy(tok_out, c->ring + slot, sizeof(int), hipMemcpyDeviceToHost));
+  }
+  return SPEC_OK;
+}
+
+extern "C" int spec_verify(spec_ctx* c, const int32_t* tokens, int n_tokens, float* logits_out) {
+  if (!c) FAIL(SPEC_E_INVAL, "null context");
+  if (!c->prefilled) FAIL(SPEC_E_STATE, "spec_prefill has not run");
+  if (n_tokens < 1 || n_tokens > SPEC_MAX_TOKENS) FAIL(SPEC_E_INVAL, "n_tokens outside 1..%d", SPEC_MAX_TOKENS);
+  ModelRt& m = c->m[SPEC_TARGET];
+  TokenSrc src;
+  src.n = n_tokens;
+  if (tokens) {
+    for (int i = 0; i < n_tokens; ++i) {
+      if (tokens[i] < 0 || tokens[i] >= m.d.vocab) FAIL(SPEC_E_INVAL, "tokens[%d] outside the vocabulary", i);
+      src.imm[i] = tokens[i];
+      src.slot[i] = 0;
+    }
+  } else {
+    if (m.len != (int)c->committed.size() - 1)
+      FAIL(SPEC_E_STATE, "target cache holds %d tokens, expected %zu", m.len, c->committed.size() - 1);
+    // the frontier, then unverified drafts: x_2.. if x_1 is the frontier, else x_1..
+    const int first = c->first_verified ? 2 : 1;
+    const int n_dr = n_tokens - 1;
+    if (first + n_dr - 1 > c->n_drafted) FAIL(SPEC_E_STATE, "%d drafts requested, %d pending", n_dr, c->n_drafted - first + 1);
+    src.imm[0] = c->committed.back();
+    src.slot[0] = 0;
+    for (int i = 0; i < n_dr; ++i) src.imm[1 + i] = -1, src.slot[1 + i] = slot_of(c, first + i);
+    if (n_dr > 0) HIPCHK(hipStreamWaitEvent(m.stream, c->ev_slot[slot_of(c, first + n_dr - 1)], 0));
+  }
+  int rc = forward(c, SPEC_TARGET, src, n_tokens);
+  if (rc) return rc;
+  c->last_verify_rows = n_tokens;
+  if (logits_out) {
+    HIPCHK(hipStreamSynchronize(m.stream));
+    HIPCHK(hipMemcpy(logits_out, m.logits, (size_t)n_tokens * m.d.vocab * sizeof(float), hipMemcpyDeviceToHost));
+  }
+  return SPEC_OK;
+}
+
+extern "C" int spec_accept(spec_ctx* c, int kind, const float* r, int n_r, float u_resample, long long force_mask,
+                           int* n_accepted, int32_t* tokens_out, int* n_out, int* next_mode, int* keep_len) {
+  if (!c || !n_accepted || !tokens_out || !n_out || !next_mode || !keep_len) FAIL(SPEC_E_INVAL, "null argument");
+  if (!(u_resample >= 0.0f && u_resample < 1.0f)) FAIL(SPEC_E_INVAL, "uniform outside [0,1)");
+  ModelRt& mt = c->m[SPEC_TARGET];
+  AcceptArgs a;
+  memset(&a, 0, sizeof(a));
+  a.kind = kind;
+  a.u_resample = u_resample;
+  a.force_mask = force_mask;
+  a.n_rows = c->last_verify_rows;
+  int first = 1;   // draft index tested by logits row 0
+  switch (kind) {
+    case SPEC_ACCEPT_AR: a.n_test = 0; break;
+    case SPEC_ACCEPT_SD: a.n_test = c->last_verify_rows - 1; first = 1; break;
+    case SPEC_ACCEPT_PRE: a.n_test = 1; first = 1; break;
+    case SPEC_ACCEPT_POST: a.n_test = c->last_verify_rows; first = 2; break;
+    default: FAIL(SPEC_E_INVAL, "unknown accept kind %d", kind);
+  }
+  if (c->last_verify_rows < 1) FAIL(SPEC_E_STATE, "no target forward to accept against");
+  if (kind == SPEC_ACCEPT_PRE && c->last_verify_rows != 1) FAIL(SPEC_E_STATE, "pre-verify needs a one-token target forward");
+  if (kind == SPEC_ACCEPT_POST && !c->first_verified) FAIL(SPEC_E_STATE, "post-verify needs an accepted first draft token");
+  if (kind != SPEC_ACCEPT_POST && kind != SPEC_ACCEPT_AR && c->first_verified) FAIL(SPEC_E_STATE, "pending drafts belong to a post-verify step");
+  if (first + a.n_test - 1 > c->n_drafted) FAIL(SPEC_E_STATE, "%d drafts to test, %d drafted", a.n_test, c->n_drafted);
+  if (a.n_test > 0 && (!r || n_r < a.n_test)) FAIL(SPEC_E_INVAL, "%d acceptance uniforms needed", a.n_test);
+  for (int i = 0; i < a.n_test; ++i) {
+    if (!(r[i] >= 0.0f && r[i] < 1.0f)) FAIL(SPEC_E_INVAL, "uniform outside [0,1)");
+    a.r[i] = r[i];
+    a.slot[i] = slot_of(c, first + i);
+  }
+  if (a.n_test > 0) HIPCHK(hipStreamWaitEvent(mt.stream, c->ev_slot[a.slot[a.n_test - 1]], 0));
+  const bool greedy = c->cfg.temperature == 0.0f;
+  const float mult = greedy ? 1.0f : c->cfg.logit_scale / c->cfg.temperature;
+  HIPCHK(launch_accept(mt.logits, mt.d.vocab, mult, greedy ? 1 : 0, c->qcache, c->ring, nullptr, a, c->accept_scratch,
+                       c->res_dev, mt.stream));
+  HIPCHK(hipMemcpyAsync(c->res_host, c->res_dev, sizeof(AcceptResult), hipMemcpyDeviceToHost, mt.stream));
+  HIPCHK(hipStreamSynchronize(mt.stream));
+  const AcceptResult& res = *c->res_host;
+  const int n = res.n_accepted;
+  int no = 0;
+  *keep_len = -1;
+  c->last_verify_rows = 0;
+  switch (kind) {
+    case SPEC_ACCEPT_AR:
+      tokens_out[no++] = res.token;
+      *next_mode = SPEC_MODE_PRE;
+      break;
+    case SPEC_ACCEPT_SD:
+      for (int i = 0; i < n; ++i) tokens_out[no++] = res.ring[a.slot[i]];
+      tokens_out[no++] = res.token;
+      *next_mode = SPEC_MODE_PRE;
+      reset_ring(c);
+      break;
+    case SPEC_ACCEPT_PRE:
+      if (n == 1) {
+        tokens_out[no++] = res.ring[a.slot[0]];
+        c->first_verified = true;
+        *next_mode = SPEC_MODE_POST;
+      } else {
+        tokens_out[no++] = res.token;
+        reset_ring(c);
+        *next_mode = SPEC_MODE_PRE;
+      }
+      break;
+    case SPEC_ACCEPT_POST:
+      for (int i = 0; i < n; ++i) tokens_out[no++] = res.ring[a.slot[i]];
+      if (n == a.n_test) {
+        c->ring_base = (c->ring_base + a.n_test) % c->ring_n;
+        c->n_drafted -= a.n_test;
+        *next_mode = SPEC_MODE_POST;
+      } else {
+        tokens_out[no++] = res.token;
+        reset_ring(c);
+        *next_mode = SPEC_MODE_PRE;
+      }
+      break;
+  }
+  for (int i = 0; i < no; ++i) c->committed.push_back(tokens_out[i]);
+  if (kind == SPEC_ACCEPT_SD || res.rejected) *keep_len = (int)c->committed.size() - 1;
+  *n_accepted = n;
+  *n_out = no;
+  return SPEC_OK;
+}
+
+extern "C" int spec_rollback_kv(spec_ctx* c, int which, int new_len) {
+  if (!c || (which != SPEC_TARGET && which != SPEC_DRAFT)) FAIL(SPEC_E_INVAL, "bad argument");
+  return rollback_model(c, which, new_len);
+}
+
+extern "C" int spec_drop_drafts(spec_ctx* c) {
+  if (!c) FAIL(SPEC_E_INVAL, "null context");
+  reset_ring(c);
+  return SPEC_OK;
+}
+
+extern "C" int spec_kv_len(const spec_ctx* c, int which) {
+  if (!c || (which != SPEC_TARGET && which != SPEC_DRAFT)) return SPEC_E_INVAL;
+  return c->m[which].len;
+}
+extern "C" int spec_committed_len(const spec_ctx* c) { return c ? (int)c->committed.size() : SPEC_E_INVAL; }
+extern "C" int spec_kv_free_pages(const spec_ctx* c, int which) {
+  if (!c || (which != SPEC_TARGET && which != SPEC_DRAFT)) return SPEC_E_INVAL;
+  return (int)c->m[which].free_pages.size();
+}
+extern "C" long long spec_forward_count(const spec_ctx* c, int which) {
+  if (!c || (which != SPEC_TARGET && which != SPEC_DRAFT)) return SPEC_E_INVAL;
+  return c->m[which].n_forwards;
+}
+
+// -------------------------------------------------------------------------------------------
+// Loops (host control flow over the calls above)
+// -------------------------------------------------------------------------------------------
+extern "C" int spec_generate(spec_ctx* c, int algo, int gamma, int n_generate, const float* u_draft,
+                             const float* r_accept, const float* u_resample, const uint8_t* force_bits,
+                             int32_t* out_tokens, double* stats) {
+  if (!c || !out_tokens || !u_resample) FAIL(SPEC_E_INVAL, "null argument");
+  if (algo < 0 || algo > 2) FAIL(SPEC_E_INVAL, "algo must be 0 (AR), 1 (SD) or 2 (PEARL)");
+  if (algo > 0 && (gamma < 1 || gamma > c->cfg.gamma_max || !u_draft || !r_accept)) FAIL(SPEC_E_INVAL, "bad gamma / uniforms");
+  if (n_generate < 1) FAIL(SPEC_E_INVAL, "n_generate must be positive");
+  if (!c->prefilled) FAIL(SPEC_E_STATE, "spec_prefill has not run");
+  const int g1 = gamma + 1;
+  int mode = SPEC_MODE_PRE;
+  int produced = 0, rc = 0;
+  long long steps = 0, accepted = 0, tested = 0, post_steps = 0;
+  const long long f0t = c->m[0].n_forwards, f0d = c->m[1].n_forwards;
+  const size_t base = c->committed.size();
+  auto t0 = std::chrono::steady_clock::now();
+  int toks[SPEC_MAX_TOKENS + 1];
+  while (produced < n_generate) {
+    const long long t = steps;
+    int n_acc = 0, n_out = 0, next_mode = SPEC_MODE_PRE, keep = -1, kind;
+    long long fm = -1;
+    int n_test = 0;
+    if (algo == 0) {
+      kind = SPEC_ACCEPT_AR;
+      if ((rc = spec_verify(c, nullptr, 1, nullptr))) return rc;
+    } else if (algo == 1) {
+      kind = SPEC_ACCEPT_SD;
+      n_test = gamma;
+      for (int i = 0; i < gamma; ++i)
+        if ((rc = spec_draft_step(c, u_draft[t * gamma + i], nullptr))) return rc;
+      if ((rc = spec_verify(c, nullptr, gamma + 1, nullptr))) return rc;
+    } else if (mode == SPEC_MODE_PRE) {
+      kind = SPEC_ACCEPT_PRE;
+      n_test = 1;
+      if ((rc = spec_verify(c, nullptr, 1, nullptr))) return rc;
+      for (int i = 0; i < gamma; ++i)
+        if ((rc = spec_draft_step(c, u_draft[t * gamma + i], nullptr))) return rc;
+    } else {
+      kind = SPEC_ACCEPT_POST;
+      n_test = gamma;
+      post_steps++;
+      if ((rc = spec_verify(c, nullptr, gamma, nullptr))) return rc;
+      for (int i = 0; i < gamma; ++i)
+        if ((rc = spec_draft_step(c, u_draft[t * gamma + i], nullptr))) return rc;
+    }
+    if (force_bits && n_test > 0) {
+      fm = 0;
+      for (int i = 0; i < n_test; ++i)
+        if (force_bits[t * g1 + i]) fm |= (1LL << i);
+    }
+    if ((rc = spec_accept(c, kind, algo ? r_accept + t * g1 : nullptr, g1, u_resample[t], fm, &n_acc, toks, &n_out,
+                          &next_mode, &keep)))
+      return rc;
+    if (keep >= 0)
+      for (int w = 0; w < 2; ++w) {
+        const int len = c->m[w].len;
+        if (len > keep && (rc = rollback_model(c, w, keep))) return rc;
+      }
+    accepted += n_acc;
+    // tokens actually tested: up to and including the first rejection
+    tested += (n_acc < n_test) ? n_acc + 1 : n_test;
+    produced += n_out;
+    mode = next_mode;
+    steps++;
+  }
+  HIPCHK(hipStreamSynchronize(c->m[0].stream));
+  HIPCHK(hipStreamSynchronize(c->m[1].stream));
+  auto t1 = std::chrono::steady_clock::now();
+  for (int i = 0; i < n_generate; ++i) out_tokens[i] = c->committed[base + i];
+  if (stats) {
+    stats[0] = (double)steps;
+    stats[1] = (double)produced;
+    stats[2] = (double)(c->m[1].n_forwards - f0d);
+    stats[3] = (double)(c->m[0].n_forwards - f0t);
+    stats[4] = (double)accepted;
+    stats[5] = (double)tested;
+    stats[6] = (double)post_steps;
+    stats[7] = std::chrono::duration<double>(t1 - t0).count();
+  }
+  return SPEC_OK;
+}
+
+// -------------------------------------------------------------------------------------------
+// Set-up helpers and single kernels
+// -------------------------------------------------------------------------------------------
+extern "C" size_t spec_packed_bytes(int N, int K) { return (size_t)(N / 16) * ((K + 31) / 32) * 1024; }
+
+extern "C" int spec_pack_weight(void* dst, const void* src, int N, int K, int panel_start, int panel_step, void* stream) {
+  if (!dst || !src) FAIL(SPEC_E_INVAL, "null pointer");
+  if (N < 16 || N % 16 || K < 8 || K % 8 || panel_start < 0 || panel_step < 1) FAIL(SPEC_E_INVAL, "N %% 16, K %% 8 required");
+  HIPCHK(launch_pack_weight(dst, src, N, K, panel_start, panel_step, (hipStream_t)stream));
+  return SPEC_OK;
+}
+
+static int check_gemm_args(int M, int N, int K) {
+  if (M < 1 || M > SPEC_MAX_TOKENS || N < 16 || N % 16 || K < 8 || K % 8)
+    FAIL(SPEC_E_INVAL, "gemm needs 1 <= M <= %d, N %% 16 == 0, K %% 8 == 0", SPEC_MAX_TOKENS);
+  return SPEC_OK;
+}
+extern "C" size_t spec_gemm_workspace_bytes(int M, int N, int K) {
+  if (check_gemm_args(M, N, K)) return 0;
+  return gemm_plan(M, N, K).partial_bytes();
+}
+extern "C" int spec_gemm_partials(const void* x, const void* w, int M, int N, int K, void* work, void* stream) {
+  if (!x || !w || !work) FAIL(SPEC_E_INVAL, "null pointer");
+  int rc = check_gemm_args(M, N, K);
+  if (rc) return rc;
+  GemmPlan p = gemm_plan(M, N, K);
+  HIPCHK(launch_gemm_partials(p, (const bf16*)x, w, (float*)work, (hipStream_t)stream));
+  return SPEC_OK;
+}
+extern "C" int spec_gemm(float* y, const void* x, const void* w, int M, int N, int K, void* work, void* stream) {
+  if (!y) FAIL(SPEC_E_INVAL, "null pointer");
+  int rc = spec_gemm_partials(x, w, M, N, K, work, stream);
+  if (rc) return rc;
+  GemmPlan p = gemm_plan(M, N, K);
+  HIPCHK(launch_reduce_partials(y, (const float*)work, p.S, (size_t)M * N, (hipStream_t)stream));
+  return SPEC_OK;
+}
+
+extern "C" int spec_read_probe(const void* src, size_t bytes, void* out, void* stream) {
+  if (!src || !out || bytes < 16) FAIL(SPEC_E_INVAL, "bad argument");
+  HIPCHK(launch_read_probe(src, bytes, out, (hipStream_t)stream));
+  return SPEC_OK;
+}
+
+extern "C" int spec_sample_row(const float* logits, int vocab, float temperature, float logit_scale, float u,
+                               float* q_out, int32_t* tok_out, void* stream) {
+  if (!logits || !q_out || !tok_out || vocab < 1) FAIL(SPEC_E_INVAL, "bad argument");
+  if (!(u >= 0.0f && u < 1.0f) || !(temperature >= 0.0f)) FAIL(SPEC_E_INVAL, "bad uniform / temperature");
+  const bool greedy = temperature == 0.0f;
+  HIPCHK(launch_sample_row(logits, vocab, greedy ? 1.0f : logit_scale / temperature, greedy ? 1 : 0, u, q_out, tok_out,
+                           (hipStream_t)stream));
+  return SPEC_OK;
+}
+
+extern "C" int spec_accept_rows(const float* p_logits, int n_rows, const float* q_rows, const int32_t* x, int n_test,
+                                int vocab, float temperature, float logit_scale, const float* r, float u_resample,
+                                int32_t* result, void* stream) {
+  if (!p_logits || !result || vocab < 1 || n_rows < 1 || n_rows > SPEC_MAX_TOKENS || n_test < 0 || n_test > n_rows)
+    FAIL(SPEC_E_INVAL, "bad argument");
+  if (n_test > 0 && (!q_rows || !x || !r)) FAIL(SPEC_E_INVAL, "null pointer");
+  AcceptArgs a;
+  memset(&a, 0, sizeof(a));
+  a.n_rows = n_rows;
+  a.n_test = n_test;
+  a.u_resample = u_resample;
+  a.force_mask = -1;
+  for (int i = 0; i < n_test; ++i) a.r[i] = r[i];
+  float* scratch = nullptr;
+  AcceptResult* res = nullptr;
+  hipStream_t st = (hipStream_t)stream;
+  if (hipMalloc((void**)&scratch, (256 + (size_t)vocab) * sizeof(float)) != hipSuccess ||
+      hipMalloc((void**)&res, sizeof(AcceptResult)) != hipSuccess) {
+    if (scratch) (void)hipFree(scratch);
+    FAIL(SPEC_E_NOMEM, "hipMalloc failed");
+  }
+  const bool greedy = temperature == 0.0f;
+  AcceptResult host;
+  hipError_t e = launch_accept(p_logits, vocab, greedy ? 1.0f : logit_scale / temperature, greedy ? 1 : 0, q_rows,
+                               nullptr, x, a, scratch, res, st);
+  if (e == hipSuccess) e = hipStreamSynchronize(st);
+  if (e == hipSuccess) e = hipMemcpy(&host, res, sizeof(host), hipMemcpyDeviceToHost);
+  (void)hipFree(scratch);
+  (void)hipFree(res);
+  if (e != hipSuccess) FAIL(SPEC_E_HIP, "accept kernels failed: %s", hipGetErrorString(e));
+  result[0] = host.n_accepted;
+  result[1] = host.token;
+  return SPEC_OK;
+}
+
+extern "C" int spec_set_profile(spec_ctx* c, int flags) {
+  if (!c) FAIL(SPEC_E_INVAL, "null context");
+  c->profile_flags = flags;
+  return SPEC_OK;
+}
+
+extern "C" int spec_profile_read(spec_ctx* c, double* ms_total, long long* n_launches, double* bytes_total) {
+  if (!c || !ms_total || !n_launches || !bytes_total) FAIL(SPEC_E_INVAL, "null argument");
+  HIPCHK(hipStreamSynchronize(c->m[0].stream));
+  double ms = 0.0;
+  for (size_t i = 0; i + 1 < c->prof.used; i += 2) {
+    float t = 0.f;
+    HIPCHK(hipEventElapsedTime(&t, c->prof.ev[i], c->prof.ev[i + 1]));
+    ms += t;
+  }
+  *ms_total = ms;
+  *n_launches = (long long)(c->prof.used / 2);
+  *bytes_total = c->prof.bytes;
+  c->prof.used = 0;
+  c->prof.bytes = 0.0;
+  return SPEC_OK;
+}

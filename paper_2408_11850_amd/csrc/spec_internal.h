@@ -1,0 +1,104 @@
+// Internal declarations shared by the kernel files and the host runtime (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <hip/hip_bf16.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "../../include/spec.h"
+
+typedef __hip_bfloat16 bf16;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+
+#define SPEC_PAGE_TOKENS 64      // tokens per KV page
+#define SPEC_RING_MAX 64         // most slots of the draft-token / q-row ring
+#define SPEC_NUM_CU 256
+
+// ---------------------------------------------------------------------------------------
+// Projection (skinny GEMM) plan: y[M][N] = x[M][K] W^T, W panel-packed.
+// The K axis is cut into S slices (one per group of workgroups) and each slice into 8
+// wave-slices of `spw` 32-wide steps; partial sums of slice s go to P[s][M][N] (fp32).
+// ---------------------------------------------------------------------------------------
+struct GemmPlan {
+  int M, N, K;
+  int steps;   // K rounded up to 32, divided by 32
+  int NT;      // N / 16 panels
+  int MT;      // 16-row tiles of x (1 or 2)
+  int S;       // K slices
+  int spw;     // steps per wave
+  int Gs;      // workgroups per slice
+  size_t partial_bytes() const { return (size_t)S * M * N * sizeof(float); }
+  size_t weight_bytes() const { return (size_t)NT * steps * 1024; }
+};
+GemmPlan gemm_plan(int M, int N, int K);
+hipError_t launch_gemm_partials(const GemmPlan& p, const bf16* x, const void* wp, float* partials, hipStream_t st);
+hipError_t launch_reduce_partials(float* y, const float* partials, int S, size_t n, hipStream_t st);
+hipError_t launch_pack_weight(void* dst, const void* src, int N, int K, int panel_start, int panel_step, hipStream_t st);
+hipError_t launch_read_probe(const void* src, size_t bytes, void* out, hipStream_t st);
+
+// ---------------------------------------------------------------------------------------
+// KV cache geometry.  Pool element order: [page][layer][k|v][kv_head][page block], where a K
+// block is [P/16 tiles][dh/32 steps][64 lanes][8] and a V block is [P/32 chunks][dh][32 slots]
+// (both already in the operand order of the 16x16x32 MFMA).
+// ---------------------------------------------------------------------------------------
+struct KvGeom {
+  int n_layers, n_kv_heads, head_dim;
+  __host__ __device__ size_t head_block() const { return (size_t)SPEC_PAGE_TOKENS * head_dim; }
+  __host__ __device__ size_t page_elems() const { return (size_t)n_layers * 2 * n_kv_heads * head_block(); }
+  __host__ __device__ size_t offset(int page, int layer, int kv, int head) const {
+    return (((size_t)page * n_layers + layer) * 2 + kv) * n_kv_heads * head_block() + (size_t)head * head_block();
+  }
+};
+
+struct TokenSrc {           // by-value kernel argument: where each input token of a forward comes from
+  int n;
+  int imm[SPEC_MAX_TOKENS];   // token id, or -1 to read ring[slot]
+  int slot[SPEC_MAX_TOKENS];
+};
+struct PageUpdate {         // by-value kernel argument: new block-table entries
+  int first, count;
+  int page[8];
+};
+
+hipError_t launch_gather_tokens(int* tok_out, const int* ring, TokenSrc src, hipStream_t st);
+hipError_t launch_set_int(int* dst, int value, hipStream_t st);
+hipError_t launch_add_int(int* dst, int delta, hipStream_t st);
+hipError_t launch_set_pages(int* block_table, PageUpdate u, hipStream_t st);
+hipError_t launch_embed(float* h, const bf16* embed, const int* tok, int M, int d, int vocab, hipStream_t st);
+// h += sum_s partials[s] (if partials), a = rmsnorm(h) * gain
+hipError_t launch_addnorm(float* h, const float* partials, int S, const bf16* gain, bf16* a, int M, int d,
+                          float eps, hipStream_t st);
+hipError_t launch_rope_append(const float* partials, int S, bf16* q, bf16* pool, const int* block_table,
+                              const int* len_ptr, KvGeom g, int layer, int M, int Hq, float theta, hipStream_t st);
+hipError_t launch_attention(const bf16* q, const bf16* pool, const int* block_table, const int* len_ptr, KvGeom g,
+                            int layer, int M, int Hq, int host_len, float* opart, float* mlpart, bf16* out,
+                            hipStream_t st);
+size_t attention_workspace_floats(int Hq, int Hkv, int dh, int max_seq);
+hipError_t launch_silu_mul(const float* partials, int S, bf16* z, int M, int F, hipStream_t st);
+
+// sampling / acceptance
+struct AcceptArgs {
+  int kind;                 // SPEC_ACCEPT_*
+  int n_rows;               // rows of target logits available
+  int n_test;               // draft tokens to test
+  int slot[SPEC_MAX_TOKENS];// ring slot of the token / q row tested against logits row i
+  float r[SPEC_MAX_TOKENS];
+  float u_resample;
+  long long force_mask;     // < 0: none
+};
+struct AcceptResult {       // device -> pinned host
+  int n_accepted;
+  int token;                // corrected / bonus / autoregressive token, -1 if none
+  int rejected;             // 1 if a rejection happened
+  int pad;
+  int ring[SPEC_RING_MAX];  // snapshot of the draft-token ring
+};
+hipError_t launch_sample_row(const float* logits, int V, float mult, int greedy, float u, float* q_out, int* tok_out,
+                             hipStream_t st);
+hipError_t launch_accept(const float* logits, int V, float mult, int greedy, const float* qcache, const int* ring,
+                         const int* x_direct, AcceptArgs a, float* stats_scratch, AcceptResult* result_dev,
+                         hipStream_t st);
+
+void spec_set_error(const char* fmt, ...);

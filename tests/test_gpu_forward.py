@@ -1,0 +1,169 @@
+"""GPU parity of the target / draft forward and of the KV cache against the oracle (run with -m gpu)."""
+import numpy as np
+import pytest
+import torch
+
+import synth
+from oracle import transformer
+from tests.util import bf16_pair, gpu_available, oracle_model
+
+pytestmark = [pytest.mark.gpu, pytest.mark.skipif(not gpu_available(), reason="needs a GPU")]
+
+LOGIT_TOL = 2e-2      # max |GPU - oracle| logit error, relative to the row's logit range (bf16 path vs fp32)
+DRAW_MARGIN_TOL = 0.02  # a draw may differ from the oracle's only if u lies this close to a CDF edge
+
+
+def _setup(cfg, gamma_max=8, temperature=1.0, extra_seq=0):
+    import paper_2408_11850_amd as amd
+    from paper_2408_11850_amd import harness
+    w = bf16_pair(cfg)
+    target, draft = harness.build_pair(cfg, weights=w)
+    ctx = harness.make_context(cfg, target, draft, gamma_max, temperature=temperature, extra_seq=extra_seq)
+    tm = oracle_model(w[0], cfg.target)
+    dm = oracle_model(w[1], cfg.draft)
+    return amd, ctx, tm, dm
+
+
+def _rel_err(got, ref):
+    rng = ref.max(axis=-1) - ref.min(axis=-1)
+    return float((np.abs(got - ref).max(axis=-1) / rng).max())
+
+
+CASES = {
+    "tiny": lambda: synth.config("tiny"),
+    "gqa64": lambda: _custom(synth.ModelShape(2, 512, 8, 2, 1376, 2048), 1),            # head_dim 64, group 4
+    "gqa128": lambda: _custom(synth.ModelShape(2, 1024, 8, 2, 2752, 4096), 1),          # head_dim 128, group 4
+    "mha128_ragged_ffn": lambda: _custom(synth.ModelShape(3, 512, 4, 4, 1392, 1008), 2),  # K not a multiple of 32
+}
+
+
+def _custom(shape, draft_layers):
+    c = synth.config("tiny")
+    c.name = "custom"
+    c.target = shape
+    c.draft = synth._truncate(shape, draft_layers)
+    c.draft_from_target_layers = draft_layers
+    c.n_prompt, c.n_generate = 200, 64
+    return c
+
+
+@pytest.mark.parametrize("case", list(CASES))
+def test_verify_logits_match_oracle(case):
+    cfg = CASES[case]()
+    print(f"forward parity case={case}", flush=True)
+    amd, ctx, tm, dm = _setup(cfg)
+    n_prompt = 150 if case != "tiny" else 32
+    prompt = synth.prompt_tokens(n_prompt, cfg.target.vocab, 7).tolist()
+    extra = synth.prompt_tokens(40, cfg.target.vocab, 8).tolist()
+    ctx.prefill(prompt)                      # chunks of 32 + a ragged tail; crosses page boundaries
+    ocm = transformer.CachedModel(tm, 512)
+    ocm.feed(prompt[:-1])
+    assert ctx.kv_len(amd.SPEC_TARGET) == n_prompt - 1 == ocm.len
+    pos = 0
+    worst = 0.0
+    for m in (1, 5, 17, 1, 9):               # pre-verify, post-verify, SD with gamma 16, ...
+        toks = ([prompt[-1]] + extra)[pos:pos + m]
+        pos += m
+        got = ctx.verify(toks, want_logits=True)
+        ref = ocm.feed(toks)
+        worst = max(worst, _rel_err(got, ref))
+    print(f"  max logit error / range = {worst:.2e}", flush=True)
+    assert worst <= LOGIT_TOL
+    assert ctx.kv_len(amd.SPEC_TARGET) == ocm.len
+    ctx.close()
+
+
+def test_multi_token_verify_equals_sequential_single_token_forwards_on_gpu():
+    cfg = CASES["gqa128"]()
+    amd, ctx, tm, dm = _setup(cfg)
+    prompt = synth.prompt_tokens(100, cfg.target.vocab, 3).tolist()
+    toks = synth.prompt_tokens(9, cfg.target.vocab, 4).tolist()
+    ctx.prefill(prompt)
+    base = ctx.kv_len(amd.SPEC_TARGET)
+    multi = ctx.verify(toks, want_logits=True)
+    ctx.rollback_kv(amd.SPEC_TARGET, base)
+    seq = np.concatenate([ctx.verify([t], want_logits=True) for t in toks])
+    # same weights, same bf16 rounding points; only the summation split differs
+    assert _rel_err(multi, seq) < 5e-3
+    ctx.close()
+
+
+def test_rollback_is_bit_exact_and_returns_pages():
+    cfg = CASES["gqa64"]()
+    amd, ctx, tm, dm = _setup(cfg, extra_seq=256)
+    prompt = synth.prompt_tokens(120, cfg.target.vocab, 5).tolist()
+    a = synth.prompt_tokens(6, cfg.target.vocab, 6).tolist()
+    junk = synth.prompt_tokens(30, cfg.target.vocab, 9).tolist()
+    ctx.prefill(prompt)
+    base = ctx.kv_len(amd.SPEC_TARGET)
+    free0 = ctx.free_pages(amd.SPEC_TARGET)
+    first = ctx.verify(a, want_logits=True)
+    ctx.verify(junk)                                    # speculate past the point, over a page boundary
+    ctx.verify(junk)
+    assert ctx.free_pages(amd.SPEC_TARGET) < free0
+    ctx.rollback_kv(amd.SPEC_TARGET, base)
+    assert ctx.free_pages(amd.SPEC_TARGET) == free0 and ctx.kv_len(amd.SPEC_TARGET) == base
+    again = ctx.verify(a, want_logits=True)
+    assert np.array_equal(first, again)                 # bit-exact
+    with pytest.raises(amd.SpecError) as e:
+        ctx.rollback_kv(amd.SPEC_TARGET, base + len(a) + 1)
+    assert e.value.code == amd.SPEC_E_INVAL
+    ctx.close()
+
+
+def test_draft_step_distribution_matches_oracle():
+    from oracle import sampling
+    cfg = CASES["tiny"]()
+    amd, ctx, tm, dm = _setup(cfg)
+    prompt = synth.prompt_tokens(32, cfg.target.vocab, 7).tolist()
+    ctx.prefill(prompt)
+    ocm = transformer.CachedModel(dm, 128)
+    ocm.feed(prompt[:-1])
+    us = synth.uniform_array(6, 5, 5).tolist()
+    inp = prompt[-1]
+    agree = 0
+    for i in range(6):
+        q = sampling.probs(ocm.feed([inp])[0], cfg.temperature, cfg.logit_scale)
+        x_ref = sampling.sample(q, us[i])
+        x = ctx.draft_step(us[i], want_token=True)
+        margin = sampling.sample_margin(q, us[i])
+        print(f"  draft step {i}: gpu {x} oracle {x_ref} margin {margin:.4f}", flush=True)
+        if x != x_ref:
+            assert margin < DRAW_MARGIN_TOL     # the chains may split only on a close draw
+            break
+        agree += 1
+        inp = x_ref
+    assert agree >= 1
+    ctx.close()
+
+
+def test_error_paths_leave_state_intact():
+    cfg = CASES["tiny"]()
+    amd, ctx, tm, dm = _setup(cfg, gamma_max=4)
+    with pytest.raises(amd.SpecError) as e:
+        ctx.verify([1])                                 # no prefill yet
+    assert e.value.code == amd.SPEC_E_STATE
+    ctx.prefill(synth.prompt_tokens(16, cfg.target.vocab, 1).tolist())
+    with pytest.raises(amd.SpecError) as e:
+        ctx.verify([cfg.target.vocab])                  # token outside the vocabulary
+    assert e.value.code == amd.SPEC_E_INVAL
+    with pytest.raises(amd.SpecError) as e:
+        ctx.verify(list(range(33)))
+    assert e.value.code == amd.SPEC_E_INVAL
+    n = ctx.kv_len(amd.SPEC_TARGET)
+    # fill the cache until pages run out: the failing call must not change the length
+    with pytest.raises(amd.SpecError) as e:
+        for _ in range(64):
+            ctx.verify(list(range(32)))
+    assert e.value.code == amd.SPEC_E_NOMEM
+    full = ctx.kv_len(amd.SPEC_TARGET)
+    assert full > n and full % 32 == n % 32
+    ctx.rollback_kv(amd.SPEC_TARGET, n)
+    ctx.verify([3, 4, 5])
+    assert ctx.kv_len(amd.SPEC_TARGET) == n + 3
+    for _ in range(8):
+        ctx.draft_step(0.5)
+    with pytest.raises(amd.SpecError) as e:
+        ctx.draft_step(0.5)                             # more than 2*gamma_max unverified drafts
+    assert e.value.code == amd.SPEC_E_STATE
+    ctx.close()

@@ -1,0 +1,199 @@
+"""GPU parity of the decoding loops (AR, SD, PEARL) against the oracle (run with -m gpu).
+
+Sampling decisions are discontinuous, so sequences are compared step by step while both sides
+agree; where they split, the oracle's decision margin for that step must be small (the bf16
+path cannot be asked to reproduce a decision closer than its logit error), and both sides
+restart from the oracle's committed tokens.
+"""
+import numpy as np
+import pytest
+import torch
+
+import synth
+from oracle import loops, transformer
+from tests.util import NpUniforms, bf16_pair, gpu_available, oracle_model
+
+pytestmark = [pytest.mark.gpu, pytest.mark.skipif(not gpu_available(), reason="needs a GPU")]
+
+MARGIN_TOL = 0.25      # a split is tolerated only on a step whose oracle margin is below this
+
+
+def _pair(cfg):
+    import paper_2408_11850_amd as amd
+    from paper_2408_11850_amd import harness
+    w = bf16_pair(cfg)
+    target, draft = harness.build_pair(cfg, weights=w)
+    return amd, harness, target, draft, oracle_model(w[0], cfg.target), oracle_model(w[1], cfg.draft)
+
+
+def _gpu_steps(amd, ctx, algo, gamma, n_generate, uni, force=None):
+    """The loop of spec_generate driven call by call; returns the tokens committed by every step."""
+    steps, mode, produced, t = [], amd.SPEC_MODE_PRE, 0, 0
+    while produced < n_generate:
+        if algo == amd.ALGO_AR:
+            kind, n_test = amd.SPEC_ACCEPT_AR, 0
+            ctx.verify(n_tokens=1)
+        elif algo == amd.ALGO_SD:
+            kind, n_test = amd.SPEC_ACCEPT_SD, gamma
+            for i in range(gamma):
+                ctx.draft_step(uni.draft[t, i])
+            ctx.verify(n_tokens=gamma + 1)
+        elif mode == amd.SPEC_MODE_PRE:
+            kind, n_test = amd.SPEC_ACCEPT_PRE, 1
+            ctx.verify(n_tokens=1)
+            for i in range(gamma):
+                ctx.draft_step(uni.draft[t, i])
+        else:
+            kind, n_test = amd.SPEC_ACCEPT_POST, gamma
+            ctx.verify(n_tokens=gamma)
+            for i in range(gamma):
+                ctx.draft_step(uni.draft[t, i])
+        fm = -1
+        if force is not None:
+            fm = sum(1 << i for i in range(n_test) if force(t, i))
+        res = ctx.accept(kind, uni.accept[t, :gamma + 1] if algo else [], uni.resample[t], fm)
+        if res["keep_len"] >= 0:
+            for w in (amd.SPEC_TARGET, amd.SPEC_DRAFT):
+                if ctx.kv_len(w) > res["keep_len"]:
+                    ctx.rollback_kv(w, res["keep_len"])
+        # invariant: the target cache lacks exactly the frontier
+        assert ctx.kv_len(amd.SPEC_TARGET) == ctx.committed_len() - 1
+        steps.append({"mode": mode, "tokens": res["tokens"], "n_accepted": res["n_accepted"]})
+        produced += len(res["tokens"])
+        mode = res["next_mode"]
+        t += 1
+    return steps
+
+
+def _oracle_steps(algo, tm, dm, prompt, n_generate, gamma, uni, cfg, temperature):
+    tr = []
+    mk = lambda m: transformer.CachedModel(m, len(prompt) + n_generate + 4 * gamma + 8)
+    kw = dict(temperature=temperature, logit_scale=cfg.logit_scale, trace=tr)
+    if algo == 0:
+        out = loops.autoregressive(mk(tm), prompt, n_generate, uni, **kw)
+        for i, s in enumerate(tr):
+            s["tokens"] = [out[i]]
+    elif algo == 1:
+        loops.speculative(mk(tm), mk(dm), prompt, n_generate, gamma, uni, **kw)
+    else:
+        loops.pearl(mk(tm), mk(dm), prompt, n_generate, gamma, uni, **kw)
+    return tr
+
+
+@pytest.mark.parametrize("algo", [0, 1, 2])
+def test_sampled_loops_follow_the_oracle_step_by_step(algo):
+    cfg = synth.config("tiny")
+    amd, harness, target, draft, tm, dm = _pair(cfg)
+    gamma, seg_len, n_total = 4, 24, 72
+    prompt = synth.prompt_tokens(cfg.n_prompt, cfg.target.vocab, cfg.seed_prompt).tolist()
+    ctx = harness.make_context(cfg, target, draft, gamma, extra_seq=n_total + 64)
+    done, segments, splits, agreed_steps, modes = 0, 0, 0, 0, set()
+    while done < n_total:
+        uni = NpUniforms(synth.make_uniforms(seg_len + 1, gamma, cfg.seed_uniform + segments))
+        print(f"algo={algo} segment={segments} prompt_len={len(prompt)}", flush=True)
+        ref = _oracle_steps(algo, tm, dm, prompt, seg_len, gamma, uni, cfg, 1.0)
+        ctx.prefill(prompt)
+        got = _gpu_steps(amd, ctx, algo, gamma, seg_len, uni)
+        k = 0
+        while k < min(len(ref), len(got)) and ref[k]["tokens"] == got[k]["tokens"]:
+            modes.add(ref[k]["mode"])
+            k += 1
+        agreed_steps += k
+        committed = [t for s in ref[:k] for t in s["tokens"]]
+        if k < min(len(ref), len(got)):
+            # first differing step: must be a close call for the oracle
+            assert ref[k]["margin"] < MARGIN_TOL, (segments, k, ref[k], got[k])
+            committed += ref[k]["tokens"]
+            splits += 1
+        prompt = prompt + committed
+        done += len(committed)
+        segments += 1
+        assert segments < 40
+    print(f"algo={algo}: {agreed_steps} steps agreed, {splits} sub-margin splits", flush=True)
+    assert agreed_steps >= 3 * max(1, splits)          # splits are the exception, not the rule
+    if algo == 2:
+        assert loops.PRE in modes and loops.POST in modes
+    ctx.close()
+
+
+def test_greedy_loops_equal_each_other_and_the_oracle():
+    cfg = synth.config("tiny")
+    amd, harness, target, draft, tm, dm = _pair(cfg)
+    gamma, n_gen = 4, 48
+    prompt = synth.prompt_tokens(cfg.n_prompt, cfg.target.vocab, cfg.seed_prompt).tolist()
+    uni = NpUniforms(synth.make_uniforms(n_gen + 1, gamma, 3))
+    ctx = harness.make_context(cfg, target, draft, gamma, temperature=0.0)
+    outs = {}
+    for algo in (amd.ALGO_AR, amd.ALGO_SD, amd.ALGO_PEARL):
+        ctx.prefill(prompt)
+        outs[algo], st = ctx.generate(algo, gamma, n_gen, uni)
+    assert outs[amd.ALGO_AR] == outs[amd.ALGO_SD] == outs[amd.ALGO_PEARL]       # lossless (Section 3.2)
+    # oracle: greedy target-only decoding; compare until the first near-tie of its top two logits
+    ocm = transformer.CachedModel(tm, 128)
+    ocm.feed(prompt[:-1])
+    tok, n_same = prompt[-1], 0
+    for i in range(n_gen):
+        lg = ocm.feed([tok])[0]
+        top2 = np.sort(lg)[-2:]
+        tok = int(np.argmax(lg))
+        if outs[amd.ALGO_AR][i] != tok:
+            assert top2[1] - top2[0] < 2e-2 * (lg.max() - lg.min())
+            break
+        n_same += 1
+    assert n_same >= 16
+    ctx.close()
+
+
+@pytest.mark.parametrize("algo", [1, 2])
+def test_two_streams_and_one_stream_give_identical_tokens(algo):
+    """Race check: overlapped draft/target streams must reproduce the serialised run bit for bit,
+    and the library's own loop must equal the call-by-call loop."""
+    cfg = synth.config("tiny")
+    amd, harness, target, draft, tm, dm = _pair(cfg)
+    gamma, n_gen = 5, 64
+    prompt = synth.prompt_tokens(cfg.n_prompt, cfg.target.vocab, 11).tolist()
+    uni = NpUniforms(synth.make_uniforms(n_gen + 1, gamma, 5))
+    outs = []
+    for serial in (True, False, False):
+        ctx = harness.make_context(cfg, target, draft, gamma, serial=serial)
+        ctx.prefill(prompt)
+        out, st = ctx.generate(algo, gamma, n_gen, uni)
+        outs.append(out)
+        if algo == 2:
+            assert st["draft_forwards"] == gamma * st["steps"] and st["target_forwards"] == st["steps"]
+        ctx.close()
+    assert outs[0] == outs[1] == outs[2]
+    ctx = harness.make_context(cfg, target, draft, gamma)
+    ctx.prefill(prompt)
+    steps = _gpu_steps(amd, ctx, algo, gamma, n_gen, uni)
+    assert [t for s in steps for t in s["tokens"]][:n_gen] == outs[0]
+    ctx.close()
+
+
+def test_figure3_trace_on_gpu():
+    """Scripted decisions of the paper's Figure 3 (gamma = 3): commits 1, 1, 3, 2; modes pre, pre, post, post."""
+    cfg = synth.config("tiny")
+    amd, harness, target, draft, tm, dm = _pair(cfg)
+    gamma = 3
+    script = [[False], [True], [True, True, True], [True, False]]
+    force = lambda t, i: script[t][i] if t < len(script) and i < len(script[t]) else True
+    prompt = synth.prompt_tokens(cfg.n_prompt, cfg.target.vocab, 2).tolist()
+    uni = NpUniforms(synth.make_uniforms(8, gamma, 1))
+    ctx = harness.make_context(cfg, target, draft, gamma)
+    ctx.prefill(prompt)
+    steps = _gpu_steps(amd, ctx, amd.ALGO_PEARL, gamma, 7, uni, force=force)
+    assert [len(s["tokens"]) for s in steps] == [1, 1, 3, 2]
+    assert [s["mode"] for s in steps] == [amd.SPEC_MODE_PRE, amd.SPEC_MODE_PRE, amd.SPEC_MODE_POST, amd.SPEC_MODE_POST]
+    assert ctx.kv_len(amd.SPEC_TARGET) == len(prompt) + 7 - 1 == ctx.kv_len(amd.SPEC_DRAFT)
+    assert ctx.forward_count(amd.SPEC_DRAFT) - ctx.forward_count(amd.SPEC_TARGET) == 4 * (gamma - 1)
+    # same script through the oracle with the same uniforms: same tokens wherever no sampling margin is tiny
+    tr = []
+    mk = lambda m: transformer.CachedModel(m, 128)
+    loops.pearl(mk(tm), mk(dm), prompt, 7, gamma, uni, temperature=1.0, logit_scale=cfg.logit_scale,
+                force=force, trace=tr)
+    for s, r in zip(steps, tr):
+        if r["margin"] > MARGIN_TOL:
+            assert s["tokens"] == r["tokens"]
+        else:
+            break
+    ctx.close()
