@@ -1,0 +1,265 @@
+#!/usr/bin/env python3
+"""Benchmark of the PEARL hot path on one MI355X.
+
+One step = one pass of the whole path: gamma draft forwards on the draft stream alongside one
+target forward on the target stream, then the fused accept / reject and the KV rollback.
+Workload (default): the 70B/7B-shape pair, bf16 random-init, 4096-token uniform prompt, temperature 1,
+window size gamma = round(T_target / T_draft) measured on the box (capped at 16).
+
+Prints ONE JSON line: decode tokens/s of PEARL over K timed steps (after W warm-up steps), the
+roofline of the dominant kernel (the target's projection kernel, HIP events around every launch of
+it in the timed region), the CPU oracle timed on a bounded sample, and side results (AR and fixed-gamma
+SD on the same kernels, forced-acceptance runs, pass-alone bandwidths).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=48)
+    ap.add_argument("--warmup", type=int, default=4)
+    ap.add_argument("--config", default="70b_7b", help="tiny | small | 7b_1b | 33b_1b | 70b_7b")
+    ap.add_argument("--gamma", type=int, default=0, help="0 = calibrate gamma = round(c) on the box")
+    ap.add_argument("--depth", type=int, default=0, help="truncate the target to this many layers (experiments)")
+    ap.add_argument("--draft-depth", type=int, default=0)
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
+    ap.add_argument("--no-side", action="store_true", help="skip AR / SD / forced-acceptance side runs")
+    return ap.parse_args()
+
+
+def forward_bytes(shape, n_ctx, m):
+    """Algorithmic HBM bytes of one forward over m tokens at context n_ctx: every projection weight once,
+    the KV cache read once, m new KV rows written, fp32 logits written."""
+    return 2 * shape.streamed_params() + n_ctx * shape.kv_bytes_per_token() + m * shape.kv_bytes_per_token() \
+        + m * shape.vocab * 4
+
+
+def timed(fn, sync):
+    sync()
+    t0 = time.perf_counter()
+    out = fn()
+    sync()
+    return out, time.perf_counter() - t0
+
+
+def cpu_baseline(cfg, gamma, device):
+    """The oracle as it stands, on the host cores, on a bounded sample: a depth-truncated pair of the
+    same widths (weights from the same generator), a short prompt, a few PEARL steps.  Per-layer times
+    are scaled to the full depths; the result is a reported baseline, not a target."""
+    import torch
+    import synth
+    from oracle import loops, transformer
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    lt, ld = (2, 1) if cfg.target.d_model >= 4096 else (min(4, cfg.target.n_layers), min(2, cfg.draft.n_layers))
+    lt, ld = min(lt, cfg.target.n_layers), min(ld, cfg.draft.n_layers)
+    small = synth.config(cfg.name, depth=lt, draft_depth=ld)
+    tw, dw = synth.make_pair(small, device=device)
+
+    def to_np(w, memo={}):
+        cv = lambda t: memo.setdefault(t.data_ptr(), t.float().cpu().numpy())
+        return {"tok_embed": cv(w["tok_embed"]), "lm_head": cv(w["lm_head"]), "final_norm": cv(w["final_norm"]),
+                "layers": [{k: cv(v) for k, v in lay.items()} for lay in w["layers"]]}
+
+    mk = lambda w, s: transformer.Model(to_np(w), s.n_heads, s.n_kv_heads, s.head_dim, s.rope_theta, s.rms_eps)
+    tm, dm = mk(tw, small.target), mk(dw, small.draft)
+    del tw, dw
+    n_prompt, n_steps = 64, 3
+    prompt = synth.prompt_tokens(n_prompt, cfg.target.vocab, cfg.seed_prompt).tolist()
+    ct, cd = transformer.CachedModel(tm, 256), transformer.CachedModel(dm, 256)
+    ct.feed(prompt[:-1]); cd.feed(prompt[:-1])
+    # time the two passes of a step separately so that they can be scaled to the full depths
+    t0 = time.perf_counter()
+    for i in range(n_steps):
+        ct.feed([prompt[i]])
+    t_target = (time.perf_counter() - t0) / n_steps
+    t0 = time.perf_counter()
+    for i in range(n_steps * 2):
+        cd.feed([prompt[i]])
+    t_draft = (time.perf_counter() - t0) / (n_steps * 2)
+    # split each into per-layer and head parts with a second measurement on the LM head alone
+    x = np.ones((1, cfg.target.d_model), dtype=np.float32)
+    t0 = time.perf_counter()
+    for _ in range(3):
+        _ = x @ tm.lm_head.T
+    t_head_t = (time.perf_counter() - t0) / 3
+    x = np.ones((1, cfg.draft.d_model), dtype=np.float32)
+    t0 = time.perf_counter()
+    for _ in range(3):
+        _ = x @ dm.lm_head.T
+    t_head_d = (time.perf_counter() - t0) / 3
+    per_layer_t = max(t_target - t_head_t, 0.0) / lt
+    per_layer_d = max(t_draft - t_head_d, 0.0) / ld
+    full_t = per_layer_t * cfg.target.n_layers + t_head_t
+    full_d = per_layer_d * cfg.draft.n_layers + t_head_d
+    # a PEARL step on the CPU runs its gamma draft forwards and its target forward one after the other;
+    # it commits at least one token, so 1 token/step is the floor used here (the GPU line reports its own rate)
+    step = full_t + gamma * full_d
+    return {"value": 1.0 / step, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": (f"oracle forward timed on a depth-truncated {cfg.name} pair ({lt} target + {ld} draft layers, "
+                       f"same widths, {n_prompt}-token context, {n_steps} target and {2 * n_steps} draft single-token "
+                       f"forwards); per-layer time x full depth + LM head; one PEARL step = 1 target + {gamma} draft "
+                       f"forwards in series, counted at its floor of 1 committed token per step"),
+            "target_forward_s": full_t, "draft_forward_s": full_d}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print(f"bench.py: this build runs on one GPU only (both models and both streams share one MI355X); "
+              f"--gpus {args.gpus} is not supported", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import synth
+    import paper_2408_11850_amd as amd
+    from paper_2408_11850_amd import harness
+    amd.load_library()
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    dev = "cuda"
+    sync = torch.cuda.synchronize
+    cfg = synth.config(args.config, depth=args.depth or None, draft_depth=args.draft_depth or None)
+    gamma_max = 16
+    log = lambda *a: print(*a, file=sys.stderr, flush=True)
+
+    (pair, t_build) = timed(lambda: harness.build_pair(cfg, dev), sync)
+    target, draft = pair
+    log(f"[bench] built {cfg.name}: target {target.nbytes() / 1e9:.2f} GB, draft {draft.nbytes() / 1e9:.2f} GB in {t_build:.1f}s")
+    ctx = harness.make_context(cfg, target, draft, gamma_max, extra_seq=64)
+    prompt = synth.prompt_tokens(cfg.n_prompt, cfg.target.vocab, cfg.seed_prompt).tolist()
+    _, t_prefill = timed(lambda: ctx.prefill(prompt), sync)
+    log(f"[bench] prefill of {cfg.n_prompt} tokens (both models): {t_prefill:.2f}s")
+    n0 = cfg.n_prompt
+
+    # ---- window size: gamma = round(c), c = T(target forward) / T(draft forward) ---------------
+    g_cal, tp, tq = harness.calibrate_gamma(ctx, n_iter=8, cap=gamma_max)
+    gamma = args.gamma or g_cal
+    log(f"[bench] target fwd {tp * 1e3:.2f} ms, draft fwd {tq * 1e3:.2f} ms, c = {tp / tq:.2f}, gamma = {gamma}")
+    ctx.rewind(n0)
+
+    # ---- each pass alone: bytes / time ---------------------------------------------------------
+    def alone(fn, n):
+        fn(); sync()
+        _, t = timed(lambda: [fn() for _ in range(n)], sync)
+        return t / n
+
+    t_v1 = alone(lambda: ctx.verify([1]), 6); ctx.rewind(n0)
+    t_vg = alone(lambda: ctx.verify(list(range(1, gamma + 1))), 6); ctx.rewind(n0)
+
+    def draft_chain():
+        ctx.draft_step(0.5)
+    t_d = alone(draft_chain, min(10, 2 * gamma_max - 2)); ctx.rewind(n0)
+    bw = lambda b, t: b / t / 1e9
+    alone_stats = {
+        "verify_m1_ms": t_v1 * 1e3, "verify_m1_GBps": bw(forward_bytes(cfg.target, n0, 1), t_v1),
+        "verify_mgamma_ms": t_vg * 1e3, "verify_mgamma_GBps": bw(forward_bytes(cfg.target, n0, gamma), t_vg),
+        "draft_ms": t_d * 1e3, "draft_GBps": bw(forward_bytes(cfg.draft, n0, 1), t_d),
+    }
+    for k in ("verify_m1", "verify_mgamma", "draft"):
+        alone_stats[k + "_frac_of_peak"] = alone_stats[k + "_GBps"] / HBM_PEAK_GBS
+    log(f"[bench] alone: {json.dumps({k: round(v, 3) for k, v in alone_stats.items()})}")
+
+    # streaming-read ceiling of this machine (plain 16-byte loads over the largest weight buffer)
+    buf = target.layers[0]["w_gateup"]
+    amd.read_probe(buf); sync()
+    _, t_rp = timed(lambda: [amd.read_probe(buf) for _ in range(10)], sync)
+    read_ceiling = buf.numel() * 2 * 10 / t_rp / 1e9
+
+    # ---- the timed region: W warm-up + K timed PEARL steps -------------------------------------
+    K, W = args.steps, args.warmup
+    uni = synth.make_uniforms(max(K, W) + 1, gamma, cfg.seed_uniform)
+    if W > 0:
+        ctx.generate(amd.ALGO_PEARL, gamma, 1 << 20, uni, max_steps=W)
+    ctx.set_profile(1)
+    ctx.profile_read()
+    sync()
+    t0 = time.perf_counter()
+    toks, st = ctx.generate(amd.ALGO_PEARL, gamma, 1 << 20, uni, max_steps=K)
+    sync()
+    elapsed = time.perf_counter() - t0
+    ms_gemm, n_gemm, bytes_gemm = ctx.profile_read()
+    ctx.set_profile(0)
+    committed = int(st["committed"])
+    value = committed / elapsed
+    step_bytes = forward_bytes(cfg.target, n0, gamma) + gamma * forward_bytes(cfg.draft, n0, 1)
+    pearl = {"tokens_per_step": committed / st["steps"], "alpha": st["accepted"] / max(st["tested"], 1),
+             "post_fraction": st["post_steps"] / st["steps"], "step_ms": elapsed / st["steps"] * 1e3,
+             "step_GBps": bw(step_bytes, elapsed / st["steps"]),
+             "overlap_efficiency": (gamma * t_d + (t_vg if st["post_steps"] else t_v1)) / (elapsed / st["steps"])}
+    log(f"[bench] PEARL: {value:.2f} tok/s, {json.dumps({k: round(v, 3) for k, v in pearl.items()})}")
+
+    side = {}
+    if not args.no_side:
+        ks = max(8, K // 3)
+        def run(algo, g, force_alpha=None, steps=ks, serial_ctx=None):
+            c = serial_ctx or ctx
+            c.rewind(n0)
+            u = synth.make_uniforms(steps + 1, g, cfg.seed_uniform)
+            fb = None
+            if force_alpha is not None:
+                fb = (synth.uniform_array((steps + 1) * (g + 1), 5, 7).view(steps + 1, g + 1).numpy() < force_alpha)
+            c.generate(algo, g, 1 << 20, u, force_bits=fb, max_steps=2)
+            sync(); t0 = time.perf_counter()
+            _, s = c.generate(algo, g, 1 << 20, u, force_bits=fb, max_steps=steps)
+            sync(); dt = time.perf_counter() - t0
+            return {"tokens_per_s": s["committed"] / dt, "tokens_per_step": s["committed"] / s["steps"],
+                    "step_ms": dt / s["steps"] * 1e3, "alpha": s["accepted"] / max(s["tested"], 1)}
+        side["ar"] = run(amd.ALGO_AR, 1, steps=max(ks, 16))
+        side["sd"] = run(amd.ALGO_SD, gamma)
+        for a in (0.5, 0.7, 0.9):
+            side[f"pearl_forced_alpha_{a}"] = run(amd.ALGO_PEARL, gamma, a)
+            side[f"sd_forced_alpha_{a}"] = run(amd.ALGO_SD, gamma, a)
+        log(f"[bench] side runs: {json.dumps(side, default=float)}")
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get(cfg.name, {}).get("gemm_target_bytes_per_launch")
+        except Exception:
+            traffic = None
+    achieved = bytes_gemm / max(ms_gemm, 1e-9) / 1e6     # bytes/ms -> GB/s
+    out = {
+        "metric": "tokens/sec at 1 GPU, 70B/7B-shape pair; verify-pass HBM GB/s % of peak",
+        "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": elapsed / max(st["steps"], 1) * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: PEARL decode, target {cfg.target.n_layers}L d={cfg.target.d_model} "
+                               f"Hq={cfg.target.n_heads} Hkv={cfg.target.n_kv_heads} F={cfg.target.d_ffn}, draft "
+                               f"{cfg.draft.n_layers}L d={cfg.draft.d_model}, V={cfg.target.vocab}, batch 1, prompt "
+                               f"{cfg.n_prompt}, temperature {cfg.temperature}, gamma {gamma} (c={tp / tq:.2f})",
+                   "gamma": gamma, "c": tp / tq, "n_prompt": cfg.n_prompt, "two_streams": True},
+        "roofline": {"bound": "hbm", "kernel": "gemm_partial_kernel<1,16,0> (target projections)",
+                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": traffic, "launches": int(n_gemm), "avg_launch_us": ms_gemm / max(n_gemm, 1) * 1e3,
+                     "avg_bytes_per_launch": bytes_gemm / max(n_gemm, 1), "read_ceiling_GBps": read_ceiling},
+        "pearl": pearl, "alone": alone_stats, "side": side,
+        "setup_s": {"build": t_build, "prefill": t_prefill},
+    }
+    if not args.no_cpu:
+        torch.cuda.synchronize()
+        out["cpu_baseline"] = cpu_baseline(cfg, gamma, dev)
+    else:
+        out["cpu_baseline"] = None
+    ctx.close()
+    print(json.dumps(out, default=float))
+
+
+if __name__ == "__main__":
+    main()

@@ -137,6 +137,11 @@ int spec_rollback_kv(spec_ctx* ctx, int which, int new_len);
 /* Forget every unverified draft token and its q row (the caller rolls the draft cache back itself). */
 int spec_drop_drafts(spec_ctx* ctx);
 
+/* Go back to the state right after the first committed_len committed tokens (prompt included):
+ * later tokens and all drafts are forgotten, both caches are cut to committed_len - 1 tokens,
+ * mode := pre-verify.  1 <= committed_len <= spec_committed_len(ctx), else SPEC_E_INVAL. */
+int spec_rewind(spec_ctx* ctx, int committed_len);
+
 int spec_kv_len(const spec_ctx* ctx, int which);     /* tokens currently in that model's cache */
 int spec_committed_len(const spec_ctx* ctx);         /* prompt + committed generated tokens    */
 int spec_kv_free_pages(const spec_ctx* ctx, int which);
@@ -145,11 +150,13 @@ long long spec_forward_count(const spec_ctx* ctx, int which); /* forwards run so
 /* Whole loops on top of the calls above (host control flow only): Algorithm 1/2 (algo 2), vanilla
  * speculative decoding (algo 1), autoregressive decoding (algo 0).  Uniform arrays are indexed
  * by step: u_draft[t*gamma + i], r_accept[t*(gamma+1) + i], u_resample[t]; each must hold
- * n_generate steps.  force_alpha < 0 uses real decisions; otherwise decision (t, i) is taken
- * from force_bits[t*(gamma+1)+i] (measurement only).  out_tokens_host receives n_generate tokens.
+ * n_generate steps.  The loop ends after n_generate tokens, or after max_steps steps if
+ * max_steps > 0.  force_bits == NULL uses real decisions; otherwise decision (t, i) is taken
+ * from force_bits[t*(gamma+1)+i] (measurement only).  out_tokens_host receives the committed
+ * tokens (at most n_generate; stats[1] tells how many were committed).
  * stats_host (nullable, 8 doubles): steps, committed, draft forwards, target forwards,
  * accepted, tested, post-verify steps, seconds. */
-int spec_generate(spec_ctx* ctx, int algo, int gamma, int n_generate, const float* u_draft,
+int spec_generate(spec_ctx* ctx, int algo, int gamma, int n_generate, int max_steps, const float* u_draft,
                   const float* r_accept, const float* u_resample, const uint8_t* force_bits,
                   int32_t* out_tokens_host, double* stats_host);
 

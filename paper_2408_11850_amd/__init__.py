@@ -55,11 +55,12 @@ SIGNATURES = {
     "spec_accept": (C.c_int, [_P, C.c_int, _PF, C.c_int, C.c_float, C.c_longlong, _PI, _PI32, _PI, _PI, _PI]),
     "spec_rollback_kv": (C.c_int, [_P, C.c_int, C.c_int]),
     "spec_drop_drafts": (C.c_int, [_P]),
+    "spec_rewind": (C.c_int, [_P, C.c_int]),
     "spec_kv_len": (C.c_int, [_P, C.c_int]),
     "spec_committed_len": (C.c_int, [_P]),
     "spec_kv_free_pages": (C.c_int, [_P, C.c_int]),
     "spec_forward_count": (C.c_longlong, [_P, C.c_int]),
-    "spec_generate": (C.c_int, [_P, C.c_int, C.c_int, C.c_int, _PF, _PF, _PF, C.POINTER(C.c_uint8), _PI32,
+    "spec_generate": (C.c_int, [_P, C.c_int, C.c_int, C.c_int, C.c_int, _PF, _PF, _PF, C.POINTER(C.c_uint8), _PI32,
                                 C.POINTER(C.c_double)]),
     "spec_last_error": (C.c_char_p, []),
     "spec_pack_weight": (C.c_int, [_P, _P, C.c_int, C.c_int, C.c_int, C.c_int, _P]),

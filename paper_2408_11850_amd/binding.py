@@ -183,6 +183,9 @@ class SpecContext:
     def drop_drafts(self):
         check(self.lib.spec_drop_drafts(self._ctx))
 
+    def rewind(self, committed_len: int):
+        check(self.lib.spec_rewind(self._ctx, committed_len))
+
     def kv_len(self, which: int) -> int:
         return check(self.lib.spec_kv_len(self._ctx, which))
 
@@ -196,28 +199,31 @@ class SpecContext:
         return int(self.lib.spec_forward_count(self._ctx, which))
 
     # ---- loops ---------------------------------------------------------------------------
-    def generate(self, algo: int, gamma: int, n_generate: int, uniforms, force_bits=None):
+    def generate(self, algo: int, gamma: int, n_generate: int, uniforms, force_bits=None, max_steps: int = 0):
         """Run AR / SD / PEARL for n_generate tokens.  `uniforms` has .draft [T,g], .accept [T,g+1], .resample [T]."""
         f32 = lambda a: np.ascontiguousarray(np.asarray(a, dtype=np.float32))
         ud, ra, ur = f32(uniforms.draft), f32(uniforms.accept), f32(uniforms.resample)
         g = max(gamma, 1)
+        need = max_steps if max_steps > 0 else n_generate      # a step commits at least one token
         if algo != ALGO_AR:
             assert ud.shape == (ud.shape[0], g) and ra.shape == (ra.shape[0], g + 1)
-            assert ud.shape[0] >= n_generate and ra.shape[0] >= n_generate
-        assert ur.shape[0] >= n_generate
+            assert ud.shape[0] >= need and ra.shape[0] >= need
+        assert ur.shape[0] >= need
         fb = None
         if force_bits is not None:
             fb = np.ascontiguousarray(np.asarray(force_bits, dtype=np.uint8))
-            assert fb.shape[0] >= n_generate and fb.shape[1] == g + 1
-        out = np.empty(n_generate, dtype=np.int32)
+            assert fb.shape[0] >= need and fb.shape[1] == g + 1
+        n_out = min(n_generate, need * (g + 1))
+        out = np.empty(n_out, dtype=np.int32)
         stats = np.zeros(8, dtype=np.float64)
         pf = lambda a: a.ctypes.data_as(C.POINTER(C.c_float))
-        check(self.lib.spec_generate(self._ctx, algo, gamma, n_generate, pf(ud), pf(ra), pf(ur),
+        check(self.lib.spec_generate(self._ctx, algo, gamma, n_out, int(max_steps), pf(ud), pf(ra), pf(ur),
                                      fb.ctypes.data_as(C.POINTER(C.c_uint8)) if fb is not None else None,
                                      out.ctypes.data_as(C.POINTER(C.c_int32)),
                                      stats.ctypes.data_as(C.POINTER(C.c_double))))
         keys = ["steps", "committed", "draft_forwards", "target_forwards", "accepted", "tested", "post_steps", "seconds"]
-        return out.tolist(), dict(zip(keys, stats.tolist()))
+        st = dict(zip(keys, stats.tolist()))
+        return out[:min(n_out, int(st["committed"]))].tolist(), st
 
     # ---- profiling -----------------------------------------------------------------------
     def set_profile(self, flags: int):

@@ -80,6 +80,7 @@ struct spec_ctx {
   bool first_verified = false;    // x_1 of the ring is already committed (it is the frontier)
   int last_verify_rows = 0;
   bool prefilled = false;
+  int mode = SPEC_MODE_PRE;       // strategy of the next PEARL step
   int profile_flags = 0;
   ProfEvents prof;
 };
@@ -218,7 +219,7 @@ int run_gemm(spec_ctx* c, int which, ModelRt& m, int M, int N, int K, const bf16
   const bool prof = (c->profile_flags & 1) && which == SPEC_TARGET;
   int rc;
   if (prof && (rc = prof_begin(c, m.stream, (double)p.weight_bytes()))) return rc;
-  HIPCHK(launch_gemm_partials(p, x, w, m.partials, m.stream));
+  HIPCHK(launch_gemm_partials(p, x, w, m.partials, m.stream, which));
   if (prof && (rc = prof_end(c, m.stream))) return rc;
   *plan_out = p;
   return SPEC_OK;
@@ -367,6 +368,7 @@ extern "C" int spec_prefill(spec_ctx* c, const int32_t* prompt, int n_prompt, in
   c->committed.assign(prompt, prompt + n_prompt);
   c->n_prompt = n_prompt;
   c->last_verify_rows = 0;
+  c->mode = SPEC_MODE_PRE;
   for (int w = 0; w < 2; ++w) {
     if (!((which_mask >> w) & 1)) continue;
     for (int s = 0; s < n_prompt - 1; s += SPEC_MAX_TOKENS) {
@@ -540,6 +542,7 @@ extern "C" int spec_accept(spec_ctx* c, int kind, const float* r, int n_r, float
   if (kind == SPEC_ACCEPT_SD || res.rejected) *keep_len = (int)c->committed.size() - 1;
   *n_accepted = n;
   *n_out = no;
+  c->mode = *next_mode;
   return SPEC_OK;
 }
 
@@ -551,6 +554,24 @@ extern "C" int spec_rollback_kv(spec_ctx* c, int which, int new_len) {
 extern "C" int spec_drop_drafts(spec_ctx* c) {
   if (!c) FAIL(SPEC_E_INVAL, "null context");
   reset_ring(c);
+  c->mode = SPEC_MODE_PRE;
+  return SPEC_OK;
+}
+
+extern "C" int spec_rewind(spec_ctx* c, int committed_len) {
+  if (!c) FAIL(SPEC_E_INVAL, "null context");
+  if (!c->prefilled) FAIL(SPEC_E_STATE, "spec_prefill has not run");
+  if (committed_len < 1 || committed_len > (int)c->committed.size())
+    FAIL(SPEC_E_INVAL, "rewind to %d outside [1, %zu]", committed_len, c->committed.size());
+  c->committed.resize(committed_len);
+  reset_ring(c);
+  c->mode = SPEC_MODE_PRE;
+  c->last_verify_rows = 0;
+  for (int w = 0; w < 2; ++w)
+    if (c->m[w].len > committed_len - 1) {
+      int rc = rollback_model(c, w, committed_len - 1);
+      if (rc) return rc;
+    }
   return SPEC_OK;
 }
 
@@ -571,7 +592,7 @@ extern "C" long long spec_forward_count(const spec_ctx* c, int which) {
 // -------------------------------------------------------------------------------------------
 // Loops (host control flow over the calls above)
 // -------------------------------------------------------------------------------------------
-extern "C" int spec_generate(spec_ctx* c, int algo, int gamma, int n_generate, const float* u_draft,
+extern "C" int spec_generate(spec_ctx* c, int algo, int gamma, int n_generate, int max_steps, const float* u_draft,
                              const float* r_accept, const float* u_resample, const uint8_t* force_bits,
                              int32_t* out_tokens, double* stats) {
   if (!c || !out_tokens || !u_resample) FAIL(SPEC_E_INVAL, "null argument");
@@ -580,14 +601,14 @@ extern "C" int spec_generate(spec_ctx* c, int algo, int gamma, int n_generate, c
   if (n_generate < 1) FAIL(SPEC_E_INVAL, "n_generate must be positive");
   if (!c->prefilled) FAIL(SPEC_E_STATE, "spec_prefill has not run");
   const int g1 = gamma + 1;
-  int mode = SPEC_MODE_PRE;
+  int mode = c->mode;
   int produced = 0, rc = 0;
   long long steps = 0, accepted = 0, tested = 0, post_steps = 0;
   const long long f0t = c->m[0].n_forwards, f0d = c->m[1].n_forwards;
   const size_t base = c->committed.size();
   auto t0 = std::chrono::steady_clock::now();
   int toks[SPEC_MAX_TOKENS + 1];
-  while (produced < n_generate) {
+  while (produced < n_generate && (max_steps <= 0 || steps < max_steps)) {
     const long long t = steps;
     int n_acc = 0, n_out = 0, next_mode = SPEC_MODE_PRE, keep = -1, kind;
     long long fm = -1;
@@ -638,7 +659,7 @@ extern "C" int spec_generate(spec_ctx* c, int algo, int gamma, int n_generate, c
   HIPCHK(hipStreamSynchronize(c->m[0].stream));
   HIPCHK(hipStreamSynchronize(c->m[1].stream));
   auto t1 = std::chrono::steady_clock::now();
-  for (int i = 0; i < n_generate; ++i) out_tokens[i] = c->committed[base + i];
+  for (int i = 0; i < n_generate && i < produced; ++i) out_tokens[i] = c->committed[base + i];
   if (stats) {
     stats[0] = (double)steps;
     stats[1] = (double)produced;
@@ -678,7 +699,7 @@ extern "C" int spec_gemm_partials(const void* x, const void* w, int M, int N, in
   int rc = check_gemm_args(M, N, K);
   if (rc) return rc;
   GemmPlan p = gemm_plan(M, N, K);
-  HIPCHK(launch_gemm_partials(p, (const bf16*)x, w, (float*)work, (hipStream_t)stream));
+  HIPCHK(launch_gemm_partials(p, (const bf16*)x, w, (float*)work, (hipStream_t)stream, 2));
   return SPEC_OK;
 }
 extern "C" int spec_gemm(float* y, const void* x, const void* w, int M, int N, int K, void* work, void* stream) {

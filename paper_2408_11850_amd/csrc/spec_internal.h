@@ -33,7 +33,8 @@ struct GemmPlan {
   size_t weight_bytes() const { return (size_t)NT * steps * 1024; }
 };
 GemmPlan gemm_plan(int M, int N, int K);
-hipError_t launch_gemm_partials(const GemmPlan& p, const bf16* x, const void* wp, float* partials, hipStream_t st);
+hipError_t launch_gemm_partials(const GemmPlan& p, const bf16* x, const void* wp, float* partials, hipStream_t st,
+                                int tag);
 hipError_t launch_reduce_partials(float* y, const float* partials, int S, size_t n, hipStream_t st);
 hipError_t launch_pack_weight(void* dst, const void* src, int N, int K, int panel_start, int panel_step, hipStream_t st);
 hipError_t launch_read_probe(const void* src, size_t bytes, void* out, hipStream_t st);
