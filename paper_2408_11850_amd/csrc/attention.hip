@@ -123,27 +123,43 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const bf16* __restrict_
   }
 }
 
-// out[i][head][e] = sum_s w_s O_s[e] / sum_s w_s l_s,  w_s = exp(m_s - max_s m_s)
+// out[i][head][e] = sum_s w_s O_s[e] / sum_s w_s l_s,  w_s = exp(m_s - max_s m_s).
+// Workgroup = (dh, 4): the four thread rows take every fourth split, then combine through LDS in a fixed order.
+#define MERGE_WAYS 4
 __global__ void attn_merge_kernel(const float* __restrict__ opart, const float* __restrict__ mlpart,
                                   bf16* __restrict__ out, int M, int Hq, int Hkv, int dh, int nsplit, int Rpad) {
-  const int i = blockIdx.x, head = blockIdx.y, e = threadIdx.x;
+  __shared__ float sm[MERGE_WAYS], snum[MERGE_WAYS][128], sden[MERGE_WAYS];
+  const int i = blockIdx.x, head = blockIdx.y, e = threadIdx.x, y = threadIdx.y;
   const int G = Hq / Hkv, kvh = head / G, Rr = i * G + head % G;
-  float mstar = NEG_BIG;
-  for (int s = 0; s < nsplit; ++s) mstar = fmaxf(mstar, mlpart[(((size_t)s * Hkv + kvh) * Rpad + Rr) * 2]);
+  float mloc = NEG_BIG;
+  for (int s = y; s < nsplit; s += MERGE_WAYS) mloc = fmaxf(mloc, mlpart[(((size_t)s * Hkv + kvh) * Rpad + Rr) * 2]);
+  if (e == 0) sm[y] = mloc;
+  __syncthreads();
+  float mstar = sm[0];
+#pragma unroll
+  for (int k = 1; k < MERGE_WAYS; ++k) mstar = fmaxf(mstar, sm[k]);
   float num = 0.f, den = 0.f;
-  for (int s = 0; s < nsplit; ++s) {
+  for (int s = y; s < nsplit; s += MERGE_WAYS) {
     const size_t row = ((size_t)s * Hkv + kvh) * Rpad + Rr;
     const float wgt = __expf(mlpart[row * 2] - mstar);
     den += wgt * mlpart[row * 2 + 1];
     num += wgt * opart[row * dh + e];
   }
-  out[((size_t)i * Hq + head) * dh + e] = __float2bfloat16(num / den);
+  snum[y][e] = num;
+  if (e == 0) sden[y] = den;
+  __syncthreads();
+  if (y == 0) {
+    float n = snum[0][e], dd = sden[0];
+#pragma unroll
+    for (int k = 1; k < MERGE_WAYS; ++k) n += snum[k][e], dd += sden[k];
+    out[((size_t)i * Hq + head) * dh + e] = __float2bfloat16(n / dd);
+  }
 }
 
 static int attn_nsplit(int Hkv, int nrt, int T) {
   const int nchunks = (T + 31) / 32;
-  int ns = (4 * SPEC_NUM_CU + Hkv * nrt - 1) / (Hkv * nrt);   // about four waves per compute unit
-  if (ns > nchunks) ns = nchunks;
+  int ns = (3 * SPEC_NUM_CU + Hkv * nrt - 1) / (Hkv * nrt);   // about three waves per compute unit ...
+  if (ns > (nchunks + 1) / 2) ns = (nchunks + 1) / 2;           // ... but at least two chunks per split
   if (ns < 1) ns = 1;
   return ns;
 }
@@ -174,6 +190,6 @@ hipError_t launch_attention(const bf16* q, const bf16* pool, const int* block_ta
                                                   opart, mlpart);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  attn_merge_kernel<<<dim3(M, Hq), dim3(dh), 0, st>>>(opart, mlpart, out, M, Hq, Hkv, dh, nsplit, Rpad);
+  attn_merge_kernel<<<dim3(M, Hq), dim3(dh, MERGE_WAYS), 0, st>>>(opart, mlpart, out, M, Hq, Hkv, dh, nsplit, Rpad);
   return hipGetLastError();
 }

@@ -58,29 +58,65 @@ __device__ __forceinline__ float block_sum(float v, float* sh) {
   return t;
 }
 
-// h[m] += sum_s P[s][m] ; a[m] = h[m] * rsqrt(mean(h[m]^2) + eps) * gain      (one workgroup per row)
-__global__ __launch_bounds__(256) void addnorm_kernel(float* __restrict__ h, const float* __restrict__ P, int S,
-                                                      const bf16* __restrict__ gain, bf16* __restrict__ a, int M,
-                                                      int d, float eps) {
-  __shared__ float sh[4];
+// h[m] += sum_s P[s][m] ; a[m] = h[m] * rsqrt(mean(h[m]^2) + eps) * gain.
+// One workgroup of 1024 threads per row; a thread keeps its (at most 4) float4 pieces of the row in
+// registers, and the S slice loads of a piece are independent, so the row is read in a few round trips.
+#define ADDNORM_THREADS 1024
+#define ADDNORM_PIECES 4      // d_model <= 4 * 4 * 1024
+__global__ __launch_bounds__(ADDNORM_THREADS) void addnorm_kernel(float* __restrict__ h, const float* __restrict__ P,
+                                                                  int S, const bf16* __restrict__ gain,
+                                                                  bf16* __restrict__ a, int M, int d, float eps) {
+  __shared__ float sh[ADDNORM_THREADS / 64];
   const int m = blockIdx.x;
-  float* hr = h + (size_t)m * d;
+  const int d4 = d >> 2;
+  f32x4* hr = reinterpret_cast<f32x4*>(h + (size_t)m * d);
+  const f32x4* P4 = reinterpret_cast<const f32x4*>(P);
+  f32x4 v[ADDNORM_PIECES];
   float ss = 0.f;
-  for (int i = threadIdx.x; i < d; i += 256) {
-    float v = hr[i];
-    if (P)
-      for (int s = 0; s < S; ++s) v += P[((size_t)s * M + m) * d + i];
-    hr[i] = v;
-    ss += v * v;
+#pragma unroll
+  for (int it = 0; it < ADDNORM_PIECES; ++it) {
+    const int i = threadIdx.x + it * ADDNORM_THREADS;
+    v[it] = f32x4{0.f, 0.f, 0.f, 0.f};
+    if (i < d4) {
+      f32x4 t = hr[i];
+      if (P) {
+        int s = 0;
+        for (; s + 4 <= S; s += 4) {   // four independent loads in flight, added in ascending slice order
+          const f32x4 p0 = P4[((size_t)(s + 0) * M + m) * d4 + i], p1 = P4[((size_t)(s + 1) * M + m) * d4 + i];
+          const f32x4 p2 = P4[((size_t)(s + 2) * M + m) * d4 + i], p3 = P4[((size_t)(s + 3) * M + m) * d4 + i];
+          t += p0; t += p1; t += p2; t += p3;
+        }
+        for (; s < S; ++s) t += P4[((size_t)s * M + m) * d4 + i];
+      }
+      hr[i] = t;
+      v[it] = t;
+      ss += t.x * t.x + t.y * t.y + t.z * t.z + t.w * t.w;
+    }
   }
-  const float tot = block_sum(ss, sh);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = ss;
+  __syncthreads();
+  float tot = 0.f;
+#pragma unroll
+  for (int i = 0; i < ADDNORM_THREADS / 64; ++i) tot += sh[i];
   const float inv = 1.0f / sqrtf(tot / (float)d + eps);
-  for (int i = threadIdx.x; i < d; i += 256)
-    a[(size_t)m * d + i] = __float2bfloat16(hr[i] * inv * __bfloat162float(gain[i]));
+#pragma unroll
+  for (int it = 0; it < ADDNORM_PIECES; ++it) {
+    const int i = threadIdx.x + it * ADDNORM_THREADS;
+    if (i < d4) {
+      const bf16* g = gain + (size_t)i * 4;
+      bf16* dst = a + (size_t)m * d + (size_t)i * 4;
+      dst[0] = __float2bfloat16(v[it].x * inv * __bfloat162float(g[0]));
+      dst[1] = __float2bfloat16(v[it].y * inv * __bfloat162float(g[1]));
+      dst[2] = __float2bfloat16(v[it].z * inv * __bfloat162float(g[2]));
+      dst[3] = __float2bfloat16(v[it].w * inv * __bfloat162float(g[3]));
+    }
+  }
 }
 hipError_t launch_addnorm(float* h, const float* partials, int S, const bf16* gain, bf16* a, int M, int d, float eps,
                           hipStream_t st) {
-  addnorm_kernel<<<M, 256, 0, st>>>(h, partials, S, gain, a, M, d, eps);
+  addnorm_kernel<<<M, ADDNORM_THREADS, 0, st>>>(h, partials, S, gain, a, M, d, eps);
   return hipGetLastError();
 }
 
