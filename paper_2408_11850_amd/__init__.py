@@ -19,6 +19,7 @@ SPEC_MODE_PRE, SPEC_MODE_POST = 0, 1
 SPEC_MAX_TOKENS = 32
 PAGE_TOKENS = 64
 ALGO_AR, ALGO_SD, ALGO_PEARL = 0, 1, 2
+SPEC_OPT_SLIM_KERNELS = 1
 
 
 class ModelDesc(C.Structure):
@@ -72,6 +73,7 @@ SIGNATURES = {
     "spec_sample_row": (C.c_int, [_P, C.c_int, C.c_float, C.c_float, C.c_float, _P, _P, _P]),
     "spec_accept_rows": (C.c_int, [_P, C.c_int, _P, _P, C.c_int, C.c_int, C.c_float, C.c_float, _PF, C.c_float,
                                    _PI32, _P]),
+    "spec_set_option": (C.c_int, [_P, C.c_int, C.c_int]),
     "spec_set_profile": (C.c_int, [_P, C.c_int]),
     "spec_profile_read": (C.c_int, [_P, C.POINTER(C.c_double), C.POINTER(C.c_longlong), C.POINTER(C.c_double)]),
 }

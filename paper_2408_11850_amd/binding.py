@@ -225,6 +225,9 @@ class SpecContext:
         st = dict(zip(keys, stats.tolist()))
         return out[:min(n_out, int(st["committed"]))].tolist(), st
 
+    def set_option(self, option: int, value: int):
+        check(self.lib.spec_set_option(self._ctx, option, value))
+
     # ---- profiling -----------------------------------------------------------------------
     def set_profile(self, flags: int):
         check(self.lib.spec_set_profile(self._ctx, flags))

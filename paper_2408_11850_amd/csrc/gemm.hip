@@ -19,13 +19,14 @@
 #define GEMM_THREADS (GEMM_WAVES * 64)
 #define GEMM_RP 4   // panels per reduction round
 
-GemmPlan gemm_plan(int M, int N, int K) {
+GemmPlan gemm_plan(int M, int N, int K, bool slim) {
   GemmPlan p;
   p.M = M; p.N = N; p.K = K;
   p.steps = (K + 31) / 32;
   p.NT = N / 16;
   p.MT = M > 16 ? 2 : 1;
-  const int spwmax = p.MT == 1 ? 16 : 8;
+  p.slim = slim && p.MT == 1;
+  const int spwmax = (p.MT == 1 && !p.slim) ? 16 : 8;
   p.S = (p.steps + GEMM_WAVES * spwmax - 1) / (GEMM_WAVES * spwmax);
   // small matrices: cut K finer until every compute unit has a workgroup
   while (p.S * p.NT < SPEC_NUM_CU && (p.steps + GEMM_WAVES * p.S * 2 - 1) / (GEMM_WAVES * p.S * 2) >= 2) p.S *= 2;
@@ -58,8 +59,11 @@ __device__ __forceinline__ void mma_chunk(f32x4 (&acc)[MT], const u32x4 (&a)[8],
 
 // TAG only names the instantiation (0 = target model, 1 = draft model, 2 = stand-alone call) so
 // that profilers list the two models' launches separately.
-template <int MT, int SPWMAX, int TAG>
-__global__ __launch_bounds__(GEMM_THREADS) void gemm_partial_kernel(const bf16* __restrict__ X,
+// WPE = waves per SIMD the register budget is sized for: 2 = "wide" (a workgroup fills its CU: best when a
+// stream runs alone), 4 = "slim" (half the K range per wave, at most 128 VGPRs, so that a workgroup of the
+// other stream's kernel fits on the same CU and the draft and target passes really overlap).
+template <int MT, int SPWMAX, int TAG, int WPE>
+__global__ __launch_bounds__(GEMM_THREADS, WPE) void gemm_partial_kernel(const bf16* __restrict__ X,
                                                                     const u32x4* __restrict__ Wp,
                                                                     float* __restrict__ P, int M, int N, int K,
                                                                     int NT, int steps, int S, int spw, int Gs) {
@@ -136,12 +140,15 @@ __global__ __launch_bounds__(GEMM_THREADS) void gemm_partial_kernel(const bf16* 
 template <int TAG>
 static void launch_tagged(const GemmPlan& p, const bf16* x, const void* wp, float* partials, hipStream_t st) {
   dim3 grid(p.Gs * p.S), block(GEMM_THREADS);
-  if (p.MT == 1)
-    gemm_partial_kernel<1, 16, TAG><<<grid, block, 0, st>>>(x, (const u32x4*)wp, partials, p.M, p.N, p.K, p.NT,
-                                                             p.steps, p.S, p.spw, p.Gs);
+  if (p.MT == 1 && p.slim)
+    gemm_partial_kernel<1, 8, TAG, 4><<<grid, block, 0, st>>>(x, (const u32x4*)wp, partials, p.M, p.N, p.K, p.NT,
+                                                               p.steps, p.S, p.spw, p.Gs);
+  else if (p.MT == 1)
+    gemm_partial_kernel<1, 16, TAG, 2><<<grid, block, 0, st>>>(x, (const u32x4*)wp, partials, p.M, p.N, p.K, p.NT,
+                                                                p.steps, p.S, p.spw, p.Gs);
   else
-    gemm_partial_kernel<2, 8, TAG><<<grid, block, 0, st>>>(x, (const u32x4*)wp, partials, p.M, p.N, p.K, p.NT,
-                                                            p.steps, p.S, p.spw, p.Gs);
+    gemm_partial_kernel<2, 8, TAG, 2><<<grid, block, 0, st>>>(x, (const u32x4*)wp, partials, p.M, p.N, p.K, p.NT,
+                                                               p.steps, p.S, p.spw, p.Gs);
 }
 
 hipError_t launch_gemm_partials(const GemmPlan& p, const bf16* x, const void* wp, float* partials, hipStream_t st,

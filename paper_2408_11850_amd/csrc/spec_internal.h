@@ -29,10 +29,11 @@ struct GemmPlan {
   int S;       // K slices
   int spw;     // steps per wave
   int Gs;      // workgroups per slice
+  bool slim;   // register-light variant that leaves half of each CU to the other stream
   size_t partial_bytes() const { return (size_t)S * M * N * sizeof(float); }
   size_t weight_bytes() const { return (size_t)NT * steps * 1024; }
 };
-GemmPlan gemm_plan(int M, int N, int K);
+GemmPlan gemm_plan(int M, int N, int K, bool slim = false);
 hipError_t launch_gemm_partials(const GemmPlan& p, const bf16* x, const void* wp, float* partials, hipStream_t st,
                                 int tag);
 hipError_t launch_reduce_partials(float* y, const float* partials, int S, size_t n, hipStream_t st);

@@ -153,21 +153,24 @@ def test_two_streams_and_one_stream_give_identical_tokens(algo):
     gamma, n_gen = 5, 64
     prompt = synth.prompt_tokens(cfg.n_prompt, cfg.target.vocab, 11).tolist()
     uni = NpUniforms(synth.make_uniforms(n_gen + 1, gamma, 5))
-    outs = []
-    for serial in (True, False, False):
-        ctx = harness.make_context(cfg, target, draft, gamma, serial=serial)
+    for slim in (0, 1):             # both projection-kernel variants; each must be race-free on its own
+        outs = []
+        for serial in (True, False, False):
+            ctx = harness.make_context(cfg, target, draft, gamma, serial=serial)
+            ctx.set_option(amd.SPEC_OPT_SLIM_KERNELS, slim)
+            ctx.prefill(prompt)
+            out, st = ctx.generate(algo, gamma, n_gen, uni)
+            outs.append(out)
+            if algo == 2:
+                assert st["draft_forwards"] == gamma * st["steps"] and st["target_forwards"] == st["steps"]
+            ctx.close()
+        assert outs[0] == outs[1] == outs[2]
+        ctx = harness.make_context(cfg, target, draft, gamma)
+        ctx.set_option(amd.SPEC_OPT_SLIM_KERNELS, slim)
         ctx.prefill(prompt)
-        out, st = ctx.generate(algo, gamma, n_gen, uni)
-        outs.append(out)
-        if algo == 2:
-            assert st["draft_forwards"] == gamma * st["steps"] and st["target_forwards"] == st["steps"]
+        steps = _gpu_steps(amd, ctx, algo, gamma, n_gen, uni)
+        assert [t for s in steps for t in s["tokens"]][:n_gen] == outs[0]
         ctx.close()
-    assert outs[0] == outs[1] == outs[2]
-    ctx = harness.make_context(cfg, target, draft, gamma)
-    ctx.prefill(prompt)
-    steps = _gpu_steps(amd, ctx, algo, gamma, n_gen, uni)
-    assert [t for s in steps for t in s["tokens"]][:n_gen] == outs[0]
-    ctx.close()
 
 
 def test_figure3_trace_on_gpu():
