@@ -34,7 +34,7 @@ def parse():
     ap.add_argument("--gamma", type=int, default=0, help="0 = calibrate gamma = round(c) on the box")
     ap.add_argument("--depth", type=int, default=0, help="truncate the target to this many layers (experiments)")
     ap.add_argument("--draft-depth", type=int, default=0)
-    ap.add_argument("--slim", type=int, default=-1, help="projection kernel variant: -1 auto, 0 wide, 1 slim")
+    ap.add_argument("--wgs", type=int, default=-1, help="projection workgroups per CU: -1 auto, 1, 2")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
     ap.add_argument("--no-side", action="store_true", help="skip AR / SD / forced-acceptance side runs")
     return ap.parse_args()
@@ -143,7 +143,7 @@ def main():
     target, draft = pair
     log(f"[bench] built {cfg.name}: target {target.nbytes() / 1e9:.2f} GB, draft {draft.nbytes() / 1e9:.2f} GB in {t_build:.1f}s")
     ctx = harness.make_context(cfg, target, draft, gamma_max, extra_seq=64)
-    ctx.set_option(amd.SPEC_OPT_SLIM_KERNELS, args.slim)
+    ctx.set_option(amd.SPEC_OPT_GEMM_WGS_PER_CU, args.wgs)
     prompt = synth.prompt_tokens(cfg.n_prompt, cfg.target.vocab, cfg.seed_prompt).tolist()
     _, t_prefill = timed(lambda: ctx.prefill(prompt), sync)
     log(f"[bench] prefill of {cfg.n_prompt} tokens (both models): {t_prefill:.2f}s")

@@ -200,12 +200,12 @@ int spec_accept_rows(const float* p_logits_dev, int n_rows, const float* q_rows_
                      int n_test, int vocab, float temperature, float logit_scale, const float* r_host,
                      float u_resample, int32_t* result_host, void* stream);
 
-/* Options.  SPEC_OPT_SLIM_KERNELS: 1 = projections use the register-light kernel variant that leaves half of
- * every compute unit to the other stream (draft and target kernels then run side by side), 0 = the
- * variant that is fastest when a stream runs alone, -1 (default) = automatic: slim inside
- * spec_generate's PEARL loop when the two streams differ, wide everywhere else.  Results are
- * bit-identical per variant but may differ between variants in the last fp32 bits (other K split). */
-enum { SPEC_OPT_SLIM_KERNELS = 1 };
+/* Options.  SPEC_OPT_GEMM_WGS_PER_CU: how many workgroups of a projection kernel are launched per compute
+ * unit.  2 fills both slots of every CU (fastest when a stream runs alone), 1 leaves one slot to the other
+ * stream's kernels so that draft and target passes run side by side, -1 (default) = automatic: spec_generate's
+ * PEARL loop on two different streams uses 1, everything else 2.  Results do not depend on it (the K split
+ * and the order of additions are fixed by the shape). */
+enum { SPEC_OPT_GEMM_WGS_PER_CU = 1 };
 int spec_set_option(spec_ctx* ctx, int option, int value);
 
 /* Run-time switches: bit 0 = record HIP events around every projection launch of the

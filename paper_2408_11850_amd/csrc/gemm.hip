@@ -17,21 +17,29 @@
 
 #define GEMM_WAVES 8
 #define GEMM_THREADS (GEMM_WAVES * 64)
+#ifndef GEMM_RP
 #define GEMM_RP 4   // panels per reduction round
+#endif
+#ifndef GEMM_LOAD
+#define GEMM_LOAD(p) __builtin_nontemporal_load(p)
+#endif
 
-GemmPlan gemm_plan(int M, int N, int K, bool slim) {
+GemmPlan gemm_plan(int M, int N, int K, int wgs_per_cu) {
   GemmPlan p;
   p.M = M; p.N = N; p.K = K;
   p.steps = (K + 31) / 32;
   p.NT = N / 16;
   p.MT = M > 16 ? 2 : 1;
-  p.slim = slim && p.MT == 1;
-  const int spwmax = (p.MT == 1 && !p.slim) ? 16 : 8;
+  if (p.MT == 2 || wgs_per_cu < 1) wgs_per_cu = 1;     // the 32-row variant needs a whole CU
+  if (wgs_per_cu > 2) wgs_per_cu = 2;
+  const int slots = SPEC_NUM_CU * wgs_per_cu;
+  const int spwmax = 8;
   p.S = (p.steps + GEMM_WAVES * spwmax - 1) / (GEMM_WAVES * spwmax);
-  // small matrices: cut K finer until every compute unit has a workgroup
-  while (p.S * p.NT < SPEC_NUM_CU && (p.steps + GEMM_WAVES * p.S * 2 - 1) / (GEMM_WAVES * p.S * 2) >= 2) p.S *= 2;
+  // small matrices: cut K finer until every workgroup slot (at two per CU) has work.  The K split depends
+  // on the shape only, never on wgs_per_cu, so both launch modes add the same numbers in the same order.
+  while (p.S * p.NT < 2 * SPEC_NUM_CU && (p.steps + GEMM_WAVES * p.S * 2 - 1) / (GEMM_WAVES * p.S * 2) >= 2) p.S *= 2;
   p.spw = (p.steps + GEMM_WAVES * p.S - 1) / (GEMM_WAVES * p.S);
-  p.Gs = SPEC_NUM_CU / p.S;
+  p.Gs = slots / p.S;
   if (p.Gs < 1) p.Gs = 1;
   if (p.Gs > p.NT) p.Gs = p.NT;
   return p;
@@ -41,7 +49,7 @@ GemmPlan gemm_plan(int M, int N, int K, bool slim) {
 __device__ __forceinline__ void load_chunk(u32x4 (&a)[8], const u32x4* __restrict__ wp, int first, int nst) {
 #pragma unroll
   for (int j = 0; j < 8; ++j)
-    if (first + j < nst) a[j] = __builtin_nontemporal_load(wp + (size_t)(first + j) * 64);
+    if (first + j < nst) a[j] = GEMM_LOAD(wp + (size_t)(first + j) * 64);
 }
 
 template <int MT, int SPWMAX, int CH>
@@ -59,9 +67,9 @@ __device__ __forceinline__ void mma_chunk(f32x4 (&acc)[MT], const u32x4 (&a)[8],
 
 // TAG only names the instantiation (0 = target model, 1 = draft model, 2 = stand-alone call) so
 // that profilers list the two models' launches separately.
-// WPE = waves per SIMD the register budget is sized for: 2 = "wide" (a workgroup fills its CU: best when a
-// stream runs alone), 4 = "slim" (half the K range per wave, at most 128 VGPRs, so that a workgroup of the
-// other stream's kernel fits on the same CU and the draft and target passes really overlap).
+// WPE = waves per SIMD the register budget is sized for.  The 16-row variant is held to 128 VGPRs (WPE 4) so
+// that two workgroups share a CU: 16 waves per CU hide the HBM latency far better than 8 (measured 6.9 vs
+// 5.9 TB/s on the gate/up matrix), and the second slot can also go to the other stream's kernel.
 template <int MT, int SPWMAX, int TAG, int WPE>
 __global__ __launch_bounds__(GEMM_THREADS, WPE) void gemm_partial_kernel(const bf16* __restrict__ X,
                                                                     const u32x4* __restrict__ Wp,
@@ -69,7 +77,8 @@ __global__ __launch_bounds__(GEMM_THREADS, WPE) void gemm_partial_kernel(const b
                                                                     int NT, int steps, int S, int spw, int Gs) {
   constexpr int NCH = SPWMAX / 8;            // chunks per panel
   constexpr int UNITS = GEMM_RP * NCH;       // chunks per reduction round (even)
-  __shared__ f32x4 red[GEMM_WAVES][GEMM_RP][MT][64];
+  constexpr int NBUF = (MT == 1) ? 2 : 1;    // LDS reduction buffers: two let a round end with a single barrier
+  __shared__ f32x4 red[NBUF][GEMM_WAVES][GEMM_RP][MT][64];
   const int s = blockIdx.x % S;
   const int idx = blockIdx.x / S;
   const int p0 = (int)((long long)idx * NT / Gs);
@@ -96,56 +105,60 @@ __global__ __launch_bounds__(GEMM_THREADS, WPE) void gemm_partial_kernel(const b
 
   const u32x4* wbase = Wp + (size_t)step0 * 64 + lane;
   const size_t pstride = (size_t)steps * 64;   // 16-byte units per panel
+  // Two-deep software pipeline over the chunk sequence (panel-major, NCH chunks per panel): chunks q and
+  // q+1 are in flight; once chunk q is consumed its buffer is refilled with chunk q+2.  The sequence runs on
+  // across reduction rounds, so the loads never drain at a round's barrier.
   u32x4 a[2][8];
-  if (p0 < p1) load_chunk(a[0], wbase + (size_t)p0 * pstride, 0, nst);
+#pragma unroll
+  for (int q = 0; q < 2; ++q)
+    if (p0 + q / NCH < p1) load_chunk(a[q], wbase + (size_t)(p0 + q / NCH) * pstride, (q % NCH) * 8, nst);
 
+  int rb = 0;
   for (int pr = p0; pr < p1; pr += GEMM_RP) {
     f32x4 acc[GEMM_RP][MT];
 #pragma unroll
     for (int rp = 0; rp < GEMM_RP; ++rp)
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) acc[rp][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
-    // software pipeline over the round's chunks: the loads of chunk u+1 (the first chunk of the
-    // next round included) are issued before the MFMAs of chunk u
 #pragma unroll
     for (int u = 0; u < UNITS; ++u) {
-      const int pn = pr + (u + 1) / NCH;
-      if (pn < p1) load_chunk(a[(u + 1) & 1], wbase + (size_t)pn * pstride, ((u + 1) % NCH) * 8, nst);
       if (pr + u / NCH < p1) {
         if (u % NCH == 0) mma_chunk<MT, SPWMAX, 0>(acc[u / NCH], a[u & 1], b, nst);
         else mma_chunk<MT, SPWMAX, (NCH > 1 ? 1 : 0)>(acc[u / NCH], a[u & 1], b, nst);
       }
+      const int pn = pr + (u + 2) / NCH;
+      if (pn < p1) load_chunk(a[u & 1], wbase + (size_t)pn * pstride, ((u + 2) % NCH) * 8, nst);
     }
 
 #pragma unroll
     for (int rp = 0; rp < GEMM_RP; ++rp)
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) red[w][rp][mt][lane] = acc[rp][mt];
+      for (int mt = 0; mt < MT; ++mt) red[rb][w][rp][mt][lane] = acc[rp][mt];
     __syncthreads();
     for (int item = threadIdx.x; item < GEMM_RP * MT * 64; item += GEMM_THREADS) {
       const int l2 = item & 63, mt = (item >> 6) % MT, rp = item / (64 * MT);
       const int p = pr + rp;
       const int m = mt * 16 + (l2 & 15);
       if (p < p1 && m < M) {
-        f32x4 t = red[0][rp][mt][l2];
+        f32x4 t = red[rb][0][rp][mt][l2];
 #pragma unroll
-        for (int ww = 1; ww < GEMM_WAVES; ++ww) t += red[ww][rp][mt][l2];
+        for (int ww = 1; ww < GEMM_WAVES; ++ww) t += red[rb][ww][rp][mt][l2];
         *reinterpret_cast<f32x4*>(P + ((size_t)s * M + m) * N + (size_t)p * 16 + (l2 >> 4) * 4) = t;
       }
     }
-    __syncthreads();
+    // with two buffers the next round writes the other one, and nobody can reach the round after that
+    // before every thread has passed the next barrier, i.e. has finished reading this buffer
+    if (NBUF == 2) rb ^= 1;
+    else __syncthreads();
   }
 }
 
 template <int TAG>
 static void launch_tagged(const GemmPlan& p, const bf16* x, const void* wp, float* partials, hipStream_t st) {
   dim3 grid(p.Gs * p.S), block(GEMM_THREADS);
-  if (p.MT == 1 && p.slim)
+  if (p.MT == 1)
     gemm_partial_kernel<1, 8, TAG, 4><<<grid, block, 0, st>>>(x, (const u32x4*)wp, partials, p.M, p.N, p.K, p.NT,
                                                                p.steps, p.S, p.spw, p.Gs);
-  else if (p.MT == 1)
-    gemm_partial_kernel<1, 16, TAG, 2><<<grid, block, 0, st>>>(x, (const u32x4*)wp, partials, p.M, p.N, p.K, p.NT,
-                                                                p.steps, p.S, p.spw, p.Gs);
   else
     gemm_partial_kernel<2, 8, TAG, 2><<<grid, block, 0, st>>>(x, (const u32x4*)wp, partials, p.M, p.N, p.K, p.NT,
                                                                p.steps, p.S, p.spw, p.Gs);

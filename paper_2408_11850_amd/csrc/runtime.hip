@@ -82,8 +82,8 @@ struct spec_ctx {
   bool prefilled = false;
   int mode = SPEC_MODE_PRE;       // strategy of the next PEARL step
   int profile_flags = 0;
-  int slim_opt = -1;              // -1 = automatic (slim inside the PEARL loop on two streams), 0 = wide, 1 = slim
-  bool slim = false;              // what the next forward uses
+  int wgs_opt = -1;               // projection workgroups per CU: -1 = automatic, 1, 2
+  int wgs = 2;                    // what the next forward uses
   ProfEvents prof;
 };
 
@@ -153,10 +153,8 @@ int init_model(ModelRt& m, const spec_model_desc& d, const spec_weights& w, cons
                             {d.d_model, d.d_ffn}, {d.vocab, d.d_model}};
   for (int mm : {1, 16, MX})
     for (auto& s : shapes) {
-      for (int sl = 0; sl < 2; ++sl) {
-        size_t b = gemm_plan(mm, s[0], s[1], sl != 0).partial_bytes();
-        if (b > pb) pb = b;
-      }
+      size_t b = gemm_plan(mm, s[0], s[1]).partial_bytes();
+      if (b > pb) pb = b;
     }
   if ((rc = dev_alloc(&m.partials, pb / sizeof(float)))) return rc;
   const size_t aw = attention_workspace_floats(d.n_heads, d.n_kv_heads, d.head_dim, m.n_pages * SPEC_PAGE_TOKENS);
@@ -219,7 +217,7 @@ int prof_end(spec_ctx* c, hipStream_t st) {
 }
 
 int run_gemm(spec_ctx* c, int which, ModelRt& m, int M, int N, int K, const bf16* x, const void* w, GemmPlan* plan_out) {
-  GemmPlan p = gemm_plan(M, N, K, c->slim);
+  GemmPlan p = gemm_plan(M, N, K, c->wgs);
   const bool prof = (c->profile_flags & 1) && which == SPEC_TARGET;
   int rc;
   if (prof && (rc = prof_begin(c, m.stream, (double)p.weight_bytes()))) return rc;
@@ -605,8 +603,8 @@ extern "C" int spec_generate(spec_ctx* c, int algo, int gamma, int n_generate, i
   if (n_generate < 1) FAIL(SPEC_E_INVAL, "n_generate must be positive");
   if (!c->prefilled) FAIL(SPEC_E_STATE, "spec_prefill has not run");
   const int g1 = gamma + 1;
-  const bool slim_before = c->slim;
-  if (c->slim_opt < 0) c->slim = (algo == 2) && (c->m[0].stream != c->m[1].stream);
+  const int wgs_before = c->wgs;
+  if (c->wgs_opt < 0) c->wgs = ((algo == 2) && (c->m[0].stream != c->m[1].stream)) ? SPEC_PEARL_WGS_PER_CU : 2;
   int mode = c->mode;
   int produced = 0, rc = 0;
   long long steps = 0, accepted = 0, tested = 0, post_steps = 0;
@@ -665,7 +663,7 @@ extern "C" int spec_generate(spec_ctx* c, int algo, int gamma, int n_generate, i
   HIPCHK(hipStreamSynchronize(c->m[0].stream));
   HIPCHK(hipStreamSynchronize(c->m[1].stream));
   auto t1 = std::chrono::steady_clock::now();
-  c->slim = slim_before;
+  c->wgs = wgs_before;
   for (int i = 0; i < n_generate && i < produced; ++i) out_tokens[i] = c->committed[base + i];
   if (stats) {
     stats[0] = (double)steps;
@@ -771,10 +769,10 @@ extern "C" int spec_accept_rows(const float* p_logits, int n_rows, const float* 
 
 extern "C" int spec_set_option(spec_ctx* c, int option, int value) {
   if (!c) FAIL(SPEC_E_INVAL, "null context");
-  if (option == SPEC_OPT_SLIM_KERNELS) {
-    if (value < -1 || value > 1) FAIL(SPEC_E_INVAL, "SPEC_OPT_SLIM_KERNELS takes -1, 0 or 1");
-    c->slim_opt = value;
-    c->slim = value == 1;
+  if (option == SPEC_OPT_GEMM_WGS_PER_CU) {
+    if (value != -1 && value != 1 && value != 2) FAIL(SPEC_E_INVAL, "SPEC_OPT_GEMM_WGS_PER_CU takes -1, 1 or 2");
+    c->wgs_opt = value;
+    c->wgs = value < 0 ? 2 : value;
     return SPEC_OK;
   }
   FAIL(SPEC_E_INVAL, "unknown option %d", option);

@@ -15,6 +15,7 @@ typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 #define SPEC_PAGE_TOKENS 64      // tokens per KV page
 #define SPEC_RING_MAX 64         // most slots of the draft-token / q-row ring
 #define SPEC_NUM_CU 256
+#define SPEC_PEARL_WGS_PER_CU 1   // projection workgroups per CU and stream while draft and target overlap
 
 // ---------------------------------------------------------------------------------------
 // Projection (skinny GEMM) plan: y[M][N] = x[M][K] W^T, W panel-packed.
@@ -29,11 +30,12 @@ struct GemmPlan {
   int S;       // K slices
   int spw;     // steps per wave
   int Gs;      // workgroups per slice
-  bool slim;   // register-light variant that leaves half of each CU to the other stream
   size_t partial_bytes() const { return (size_t)S * M * N * sizeof(float); }
   size_t weight_bytes() const { return (size_t)NT * steps * 1024; }
 };
-GemmPlan gemm_plan(int M, int N, int K, bool slim = false);
+// wgs_per_cu: 2 = fill both workgroup slots of every CU (a stream running alone), 1 = leave one slot to
+// the other stream's kernels.  The K split (S, spw) does not depend on it.
+GemmPlan gemm_plan(int M, int N, int K, int wgs_per_cu = 2);
 hipError_t launch_gemm_partials(const GemmPlan& p, const bf16* x, const void* wp, float* partials, hipStream_t st,
                                 int tag);
 hipError_t launch_reduce_partials(float* y, const float* partials, int S, size_t n, hipStream_t st);

@@ -153,11 +153,11 @@ def test_two_streams_and_one_stream_give_identical_tokens(algo):
     gamma, n_gen = 5, 64
     prompt = synth.prompt_tokens(cfg.n_prompt, cfg.target.vocab, 11).tolist()
     uni = NpUniforms(synth.make_uniforms(n_gen + 1, gamma, 5))
-    for slim in (0, 1):             # both projection-kernel variants; each must be race-free on its own
+    for slim in (1, 2):             # one or two projection workgroups per CU: same numbers, both race-free
         outs = []
         for serial in (True, False, False):
             ctx = harness.make_context(cfg, target, draft, gamma, serial=serial)
-            ctx.set_option(amd.SPEC_OPT_SLIM_KERNELS, slim)
+            ctx.set_option(amd.SPEC_OPT_GEMM_WGS_PER_CU, slim)
             ctx.prefill(prompt)
             out, st = ctx.generate(algo, gamma, n_gen, uni)
             outs.append(out)
@@ -166,7 +166,7 @@ def test_two_streams_and_one_stream_give_identical_tokens(algo):
             ctx.close()
         assert outs[0] == outs[1] == outs[2]
         ctx = harness.make_context(cfg, target, draft, gamma)
-        ctx.set_option(amd.SPEC_OPT_SLIM_KERNELS, slim)
+        ctx.set_option(amd.SPEC_OPT_GEMM_WGS_PER_CU, slim)
         ctx.prefill(prompt)
         steps = _gpu_steps(amd, ctx, algo, gamma, n_gen, uni)
         assert [t for s in steps for t in s["tokens"]][:n_gen] == outs[0]
