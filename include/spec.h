@@ -204,8 +204,10 @@ int spec_accept_rows(const float* p_logits_dev, int n_rows, const float* q_rows_
  * unit.  2 fills both slots of every CU (fastest when a stream runs alone), 1 leaves one slot to the other
  * stream's kernels so that draft and target passes run side by side, -1 (default) = automatic: spec_generate's
  * PEARL loop on two different streams uses 1, everything else 2.  Results do not depend on it (the K split
- * and the order of additions are fixed by the shape). */
-enum { SPEC_OPT_GEMM_WGS_PER_CU = 1 };
+ * and the order of additions are fixed by the shape).
+ * SPEC_OPT_GRAPHS: 1 (default) = every forward is captured once per (model, token count, mode) into a HIP graph
+ * and replayed; 0 = launch kernel by kernel.  Results are identical. */
+enum { SPEC_OPT_GEMM_WGS_PER_CU = 1, SPEC_OPT_GRAPHS = 2 };
 int spec_set_option(spec_ctx* ctx, int option, int value);
 
 /* Run-time switches: bit 0 = record HIP events around every projection launch of the

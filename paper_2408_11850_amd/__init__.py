@@ -20,6 +20,7 @@ SPEC_MAX_TOKENS = 32
 PAGE_TOKENS = 64
 ALGO_AR, ALGO_SD, ALGO_PEARL = 0, 1, 2
 SPEC_OPT_GEMM_WGS_PER_CU = 1
+SPEC_OPT_GRAPHS = 2
 
 
 class ModelDesc(C.Structure):

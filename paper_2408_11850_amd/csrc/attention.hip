@@ -173,12 +173,13 @@ size_t attention_workspace_floats(int Hq, int Hkv, int dh, int max_seq) {
 }
 
 hipError_t launch_attention(const bf16* q, const bf16* pool, const int* block_table, const int* len_ptr, KvGeom g,
-                            int layer, int M, int Hq, int host_len, float* opart, float* mlpart, bf16* out,
+                            int layer, int M, int Hq, int split_tokens, float* opart, float* mlpart, bf16* out,
                             hipStream_t st) {
   const int Hkv = g.n_kv_heads, G = Hq / Hkv, R = M * G, dh = g.head_dim;
   const int nrt = (R + 15) / 16;
   const int Rpad = ((SPEC_MAX_TOKENS * G + 15) / 16) * 16;
-  const int nsplit = attn_nsplit(Hkv, nrt, host_len + M);
+  // the split count is sized for the longest context, not the current one, so that the launch is replayable
+  const int nsplit = attn_nsplit(Hkv, nrt, split_tokens);
   const int wpb = nrt < 4 ? nrt : 4;
   dim3 grid((nrt + wpb - 1) / wpb, Hkv, nsplit), block(64 * wpb);
   const float scale = 1.0f / sqrtf((float)dh);

@@ -53,6 +53,9 @@ struct ModelRt {
   bf16 *a = nullptr, *qbuf = nullptr, *attn_out = nullptr, *z = nullptr;
   float *partials = nullptr, *opart = nullptr, *mlpart = nullptr, *logits = nullptr;
   long long n_forwards = 0;
+  int split_tokens = 0;           // context length the attention split count is sized for (fixed per context)
+  // captured forwards, keyed [tokens][logit mode 0/1/2][projection workgroups per CU]
+  hipGraphExec_t graphs[SPEC_MAX_TOKENS + 1][3][3] = {};
 };
 
 struct ProfEvents {
@@ -82,6 +85,7 @@ struct spec_ctx {
   bool prefilled = false;
   int mode = SPEC_MODE_PRE;       // strategy of the next PEARL step
   int profile_flags = 0;
+  bool use_graphs = true;         // replay captured forwards instead of launching ~10 kernels per layer
   int wgs_opt = -1;               // projection workgroups per CU: -1 = automatic, 1, 2
   int wgs = 2;                    // what the next forward uses
   ProfEvents prof;
@@ -128,6 +132,7 @@ int init_model(ModelRt& m, const spec_model_desc& d, const spec_weights& w, cons
   }
   m.geom.n_layers = d.n_layers; m.geom.n_kv_heads = d.n_kv_heads; m.geom.head_dim = d.head_dim;
   m.n_pages = (cfg.max_seq + SPEC_PAGE_TOKENS - 1) / SPEC_PAGE_TOKENS + 1;
+  m.split_tokens = m.n_pages * SPEC_PAGE_TOKENS;
   int rc;
   const size_t pool_elems = (size_t)m.n_pages * m.geom.page_elems();
   if ((rc = dev_alloc(&m.pool, pool_elems))) return rc;
@@ -165,6 +170,13 @@ int init_model(ModelRt& m, const spec_model_desc& d, const spec_weights& w, cons
 }
 
 void free_model(ModelRt& m) {
+  for (auto& a : m.graphs)
+    for (auto& b : a)
+      for (hipGraphExec_t& g : b)
+        if (g) {
+          (void)hipGraphExecDestroy(g);
+          g = nullptr;
+        }
   void* ptrs[] = {m.pool, m.block_table_dev, m.len_dev, m.tok_in, m.h, m.a, m.qbuf, m.attn_out, m.z, m.partials,
                   m.opart, m.logits};
   for (void* p : ptrs)
@@ -227,16 +239,14 @@ int run_gemm(spec_ctx* c, int which, ModelRt& m, int M, int N, int K, const bf16
   return SPEC_OK;
 }
 
-// One forward of model `which` over M tokens.  logit_rows: 0 = none (prefill), 1 = last row only, M = all rows.
-int forward(spec_ctx* c, int which, const TokenSrc& src, int logit_rows) {
+// The kernel chain of one forward over the M tokens in m.tok_in.  Nothing here depends on host state other
+// than M, logit_rows and the launch mode: positions come from *len_dev, pages from the device block table,
+// so the chain can be captured once into a HIP graph and replayed.
+int enqueue_forward(spec_ctx* c, int which, int M, int logit_rows) {
   ModelRt& m = c->m[which];
   const spec_model_desc& d = m.d;
-  const int M = src.n;
-  if (M < 1 || M > SPEC_MAX_TOKENS) FAIL(SPEC_E_INVAL, "forward over %d tokens (1..%d allowed)", M, SPEC_MAX_TOKENS);
-  int rc;
-  if ((rc = ensure_pages(m, m.len + M))) return rc;
   hipStream_t st = m.stream;
-  HIPCHK(launch_gather_tokens(m.tok_in, c->ring, src, st));
+  int rc;
   HIPCHK(launch_embed(m.h, (const bf16*)m.tok_embed, m.tok_in, M, d.d_model, d.vocab, st));
   const int qkvN = (d.n_heads + 2 * d.n_kv_heads) * d.head_dim;
   const int HD = d.n_heads * d.head_dim;
@@ -248,8 +258,8 @@ int forward(spec_ctx* c, int which, const TokenSrc& src, int logit_rows) {
     if ((rc = run_gemm(c, which, m, M, qkvN, d.d_model, m.a, m.wqkv[l], &p))) return rc;
     HIPCHK(launch_rope_append(m.partials, p.S, m.qbuf, m.pool, m.block_table_dev, m.len_dev, m.geom, l, M, d.n_heads,
                               d.rope_theta, st));
-    HIPCHK(launch_attention(m.qbuf, m.pool, m.block_table_dev, m.len_dev, m.geom, l, M, d.n_heads, m.len, m.opart,
-                            m.mlpart, m.attn_out, st));
+    HIPCHK(launch_attention(m.qbuf, m.pool, m.block_table_dev, m.len_dev, m.geom, l, M, d.n_heads, m.split_tokens,
+                            m.opart, m.mlpart, m.attn_out, st));
     if ((rc = run_gemm(c, which, m, M, d.d_model, HD, m.attn_out, m.wo[l], &p))) return rc;
     HIPCHK(launch_addnorm(m.h, m.partials, p.S, (const bf16*)m.ffn_norm[l], m.a, M, d.d_model, d.rms_eps, st));
     if ((rc = run_gemm(c, which, m, M, 2 * d.d_ffn, d.d_model, m.a, m.wgu[l], &p))) return rc;
@@ -266,6 +276,42 @@ int forward(spec_ctx* c, int which, const TokenSrc& src, int logit_rows) {
     HIPCHK(launch_reduce_partials(m.logits, m.partials, p.S, (size_t)rows * d.vocab, st));
   }
   HIPCHK(launch_add_int(m.len_dev, M, st));
+  return SPEC_OK;
+}
+
+// One forward of model `which` over M tokens.  logit_rows: 0 = none (prefill), 1 = last row only, M = all rows.
+int forward(spec_ctx* c, int which, const TokenSrc& src, int logit_rows) {
+  ModelRt& m = c->m[which];
+  const int M = src.n;
+  if (M < 1 || M > SPEC_MAX_TOKENS) FAIL(SPEC_E_INVAL, "forward over %d tokens (1..%d allowed)", M, SPEC_MAX_TOKENS);
+  int rc;
+  if ((rc = ensure_pages(m, m.len + M))) return rc;
+  hipStream_t st = m.stream;
+  HIPCHK(launch_gather_tokens(m.tok_in, c->ring, src, st));
+  if (c->use_graphs && !(c->profile_flags & 1)) {
+    const int lm = logit_rows == 0 ? 0 : (logit_rows >= M ? 2 : 1);
+    hipGraphExec_t& ge = m.graphs[M][lm][c->wgs];
+    if (!ge) {
+      HIPCHK(hipStreamBeginCapture(st, hipStreamCaptureModeRelaxed));
+      rc = enqueue_forward(c, which, M, logit_rows);
+      hipGraph_t g = nullptr;
+      hipError_t e = hipStreamEndCapture(st, &g);   // always leave capture mode, also after a failed launch
+      if (rc || e != hipSuccess) {
+        if (g) (void)hipGraphDestroy(g);
+        if (!rc) FAIL(SPEC_E_HIP, "hipStreamEndCapture failed: %s", hipGetErrorString(e));
+        return rc;
+      }
+      e = hipGraphInstantiate(&ge, g, nullptr, nullptr, 0);
+      (void)hipGraphDestroy(g);
+      if (e != hipSuccess) {
+        ge = nullptr;
+        FAIL(SPEC_E_HIP, "hipGraphInstantiate failed: %s", hipGetErrorString(e));
+      }
+    }
+    HIPCHK(hipGraphLaunch(ge, st));
+  } else if ((rc = enqueue_forward(c, which, M, logit_rows))) {
+    return rc;
+  }
   m.len += M;
   m.n_forwards++;
   return SPEC_OK;
@@ -773,6 +819,11 @@ extern "C" int spec_set_option(spec_ctx* c, int option, int value) {
     if (value != -1 && value != 1 && value != 2) FAIL(SPEC_E_INVAL, "SPEC_OPT_GEMM_WGS_PER_CU takes -1, 1 or 2");
     c->wgs_opt = value;
     c->wgs = value < 0 ? 2 : value;
+    return SPEC_OK;
+  }
+  if (option == SPEC_OPT_GRAPHS) {
+    if (value != 0 && value != 1) FAIL(SPEC_E_INVAL, "SPEC_OPT_GRAPHS takes 0 or 1");
+    c->use_graphs = value == 1;
     return SPEC_OK;
   }
   FAIL(SPEC_E_INVAL, "unknown option %d", option);

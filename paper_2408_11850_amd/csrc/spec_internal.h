@@ -77,7 +77,7 @@ hipError_t launch_addnorm(float* h, const float* partials, int S, const bf16* ga
 hipError_t launch_rope_append(const float* partials, int S, bf16* q, bf16* pool, const int* block_table,
                               const int* len_ptr, KvGeom g, int layer, int M, int Hq, float theta, hipStream_t st);
 hipError_t launch_attention(const bf16* q, const bf16* pool, const int* block_table, const int* len_ptr, KvGeom g,
-                            int layer, int M, int Hq, int host_len, float* opart, float* mlpart, bf16* out,
+                            int layer, int M, int Hq, int split_tokens, float* opart, float* mlpart, bf16* out,
                             hipStream_t st);
 size_t attention_workspace_floats(int Hq, int Hkv, int dh, int max_seq);
 hipError_t launch_silu_mul(const float* partials, int S, bf16* z, int M, int F, hipStream_t st);

@@ -167,3 +167,41 @@ def test_error_paths_leave_state_intact():
         ctx.draft_step(0.5)                             # more than 2*gamma_max unverified drafts
     assert e.value.code == amd.SPEC_E_STATE
     ctx.close()
+
+
+def test_graph_replays_equal_kernel_by_kernel_launches():
+    """Captured forwards (HIP graphs) are replayed several times, with eager forwards, rollbacks and
+    synchronisations in between; every replay must equal the kernel-by-kernel result bit for bit."""
+    import torch
+    cfg = CASES["gqa128"]()
+    amd, ctx, tm, dm = _setup(cfg, extra_seq=256)
+    prompt = synth.prompt_tokens(140, cfg.target.vocab, 21).tolist()
+    toks = synth.prompt_tokens(64, cfg.target.vocab, 22).tolist()
+    ctx.prefill(prompt)
+    base = ctx.kv_len(amd.SPEC_TARGET)
+
+    def run(graphs, rounds):
+        ctx.set_option(amd.SPEC_OPT_GRAPHS, graphs)
+        out = []
+        for r in range(rounds):
+            ctx.rollback_kv(amd.SPEC_TARGET, base)
+            out.append(ctx.verify(toks[0:5], want_logits=True))          # M = 5
+            out.append(ctx.verify(toks[5:6], want_logits=True))          # M = 1
+            out.append(ctx.verify(toks[6:11], want_logits=True))         # M = 5 again, other position
+            torch.cuda.synchronize()
+        return out
+
+    eager = run(0, 1)
+    replays = run(1, 3)                      # first round captures, later rounds replay
+    mixed = run(0, 1) + run(1, 1)            # eager work between replays
+    for i, got in enumerate(replays + mixed):
+        assert np.array_equal(got, eager[i % 3]), i
+    # the draft chain through graphs equals the eager chain as well
+    outs = []
+    for graphs in (0, 1, 1):
+        ctx.set_option(amd.SPEC_OPT_GRAPHS, graphs)
+        ctx.rewind(len(prompt))
+        outs.append([ctx.draft_step(u, want_token=True) for u in (0.11, 0.52, 0.93, 0.34)])
+        ctx.drop_drafts()
+    assert outs[0] == outs[1] == outs[2]
+    ctx.close()
