@@ -1,0 +1,93 @@
+// Stand-alone driver for profiling the projection kernel without Python: runs spec_gemm_partials on the
+// five projection shapes of a model (default: the 70B-shape target) at a given token count, plus the
+// streaming-read probe and the weight-packing copy kernel as calibration launches of known size.
+// Weights are a constant byte pattern (traffic and timing do not depend on the values).
+//
+//   gemm_probe [M=7] [iters=5] [d_model=8192] [n_heads=64] [n_kv_heads=8] [d_ffn=28672] [vocab=32000]
+//
+// Used under `rocprofv3 --kernel-trace --stats` and `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE`.
+#include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <cstdlib>
+#include <vector>
+
+#include "../../include/spec.h"
+
+#define CK(x)                                                                  \
+  do {                                                                         \
+    hipError_t e_ = (x);                                                       \
+    if (e_ != hipSuccess) {                                                    \
+      fprintf(stderr, "%s: %s\n", #x, hipGetErrorString(e_));                  \
+      return 1;                                                                \
+    }                                                                          \
+  } while (0)
+#define SK(x)                                                                  \
+  do {                                                                         \
+    int r_ = (x);                                                              \
+    if (r_ != SPEC_OK) {                                                       \
+      fprintf(stderr, "%s: %d %s\n", #x, r_, spec_last_error());               \
+      return 1;                                                                \
+    }                                                                          \
+  } while (0)
+
+int main(int argc, char** argv) {
+  const int M = argc > 1 ? atoi(argv[1]) : 7;
+  const int iters = argc > 2 ? atoi(argv[2]) : 5;
+  const int d = argc > 3 ? atoi(argv[3]) : 8192;
+  const int hq = argc > 4 ? atoi(argv[4]) : 64;
+  const int hkv = argc > 5 ? atoi(argv[5]) : 8;
+  const int F = argc > 6 ? atoi(argv[6]) : 28672;
+  const int V = argc > 7 ? atoi(argv[7]) : 32000;
+  const int dh = d / hq;
+  struct Shape { const char* name; int N, K; };
+  const Shape shapes[] = {{"qkv", (hq + 2 * hkv) * dh, d}, {"o", d, hq * dh}, {"gate_up", 2 * F, d},
+                          {"down", d, F}, {"lm_head", V, d}};
+  hipStream_t st;
+  CK(hipStreamCreate(&st));
+  size_t max_w = 0, max_work = 0, max_x = 0;
+  for (const Shape& s : shapes) {
+    size_t b = spec_packed_bytes(s.N, s.K);
+    if (b > max_w) max_w = b;
+    size_t w = spec_gemm_workspace_bytes(M, s.N, s.K);
+    if (w > max_work) max_work = w;
+    if ((size_t)M * s.K * 2 > max_x) max_x = (size_t)M * s.K * 2;
+  }
+  // two weight buffers used alternately, so that a launch never finds its matrix in a cache
+  void *w[2], *x, *work, *out, *rowmajor;
+  CK(hipMalloc(&w[0], max_w));
+  CK(hipMalloc(&w[1], max_w));
+  CK(hipMalloc(&rowmajor, max_w));
+  CK(hipMalloc(&x, max_x));
+  CK(hipMalloc(&work, max_work));
+  CK(hipMalloc(&out, 256));
+  CK(hipMemset(w[0], 0x3c, max_w));
+  CK(hipMemset(w[1], 0x3c, max_w));
+  CK(hipMemset(rowmajor, 0x3c, max_w));
+  CK(hipMemset(x, 0x3c, max_x));
+  CK(hipMemset(out, 0, 256));
+  CK(hipDeviceSynchronize());
+  hipEvent_t e0, e1;
+  CK(hipEventCreate(&e0));
+  CK(hipEventCreate(&e1));
+  printf("projection probe: M=%d, %d launches per shape\n", M, iters);
+  for (const Shape& s : shapes) {
+    const size_t bytes = spec_packed_bytes(s.N, s.K);
+    SK(spec_gemm_partials(x, w[0], M, s.N, s.K, work, st));   // warm-up
+    CK(hipEventRecord(e0, st));
+    for (int i = 0; i < iters; ++i) SK(spec_gemm_partials(x, w[(i + 1) & 1], M, s.N, s.K, work, st));
+    CK(hipEventRecord(e1, st));
+    CK(hipStreamSynchronize(st));
+    float ms = 0.f;
+    CK(hipEventElapsedTime(&ms, e0, e1));
+    printf("  %-8s N=%6d K=%6d  weight %9.3f MB  %8.2f us  %7.1f GB/s\n", s.name, s.N, s.K, bytes / 1e6,
+           ms / iters * 1e3, bytes / (ms / iters * 1e-3) / 1e9);
+  }
+  // calibration launches of known size: a pure read of max_w bytes, and a copy (read + write) of the gate/up matrix
+  for (int i = 0; i < 3; ++i) SK(spec_read_probe(w[i & 1], max_w, out, st));
+  for (int i = 0; i < 3; ++i) SK(spec_pack_weight(w[i & 1], rowmajor, 2 * F, d, 0, 1, st));
+  CK(hipStreamSynchronize(st));
+  printf("calibration: read_probe_kernel reads %zu bytes; pack_weight_kernel reads and writes %zu bytes\n", max_w,
+         spec_packed_bytes(2 * F, d));
+  return 0;
+}
