@@ -8,26 +8,21 @@
 // A wave therefore reads its share of a panel as consecutive fully-coalesced 1 KiB loads.
 //
 // Work split: the K axis is cut into S slices; a workgroup of 8 waves owns one slice and a
-// contiguous range of panels; wave w owns `spw` <= 8 consecutive steps of the slice and keeps the
+// contiguous range of panels; wave w owns `spw` consecutive steps of the slice and keeps the
 // matching activation fragments (the B operand) in registers for the whole kernel.  After every
-// round of 4 panels the 8 wave-partials are summed through LDS in a fixed order.
-//
-// What happens to the sums (EPI) and where the activations come from (PRO) is fused in:
-//   PRO_BF16  x is bf16 [M][K];            PRO_NORM  x = rmsnorm(h) * gain computed while loading h (fp32)
-//   EPI_PARTIAL  write the K-slice partial P[s][m][n] (the consumer adds the slices)
-//   EPI_F32      y[m][n] = sum            EPI_RESID  h[m][n] += sum, and sum_n h^2 per row for the next norm
-//   EPI_SILU     z[m][f] = silu(gate) * up with gate / up in alternating panels
-// With S > 1 the fused epilogues need all K slices: every workgroup writes its partial, and the last of the
-// S workgroups that share a panel range to arrive (an atomic counter, no waiting) adds the slices in ascending
-// order and applies the epilogue.  All additions happen in an order fixed by the shape, so results are
-// bit-reproducible and do not depend on which workgroup arrives last.
+// round of 4 panels the 8 wave-partials are summed through LDS in a fixed order and written to
+// P[s][m][n] (fp32).  Consumers add the S slices in ascending order, so results do not depend
+// on timing.
 #include "spec_internal.h"
 
 #define GEMM_WAVES 8
 #define GEMM_THREADS (GEMM_WAVES * 64)
-#define GEMM_SPW 8    // most K steps per wave (32 VGPRs of activation fragments per 16 rows)
-#define GEMM_RP 4     // panels per reduction round
+#ifndef GEMM_RP
+#define GEMM_RP 4   // panels per reduction round
+#endif
+#ifndef GEMM_LOAD
 #define GEMM_LOAD(p) __builtin_nontemporal_load(p)
+#endif
 
 GemmPlan gemm_plan(int M, int N, int K, int wgs_per_cu) {
   GemmPlan p;
@@ -38,125 +33,86 @@ GemmPlan gemm_plan(int M, int N, int K, int wgs_per_cu) {
   if (p.MT == 2 || wgs_per_cu < 1) wgs_per_cu = 1;     // the 32-row variant needs a whole CU
   if (wgs_per_cu > 2) wgs_per_cu = 2;
   const int slots = SPEC_NUM_CU * wgs_per_cu;
-  p.S = (p.steps + GEMM_WAVES * GEMM_SPW - 1) / (GEMM_WAVES * GEMM_SPW);
+  const int spwmax = 8;
+  p.S = (p.steps + GEMM_WAVES * spwmax - 1) / (GEMM_WAVES * spwmax);
   // small matrices: cut K finer until every workgroup slot (at two per CU) has work.  The K split depends
   // on the shape only, never on wgs_per_cu, so both launch modes add the same numbers in the same order.
   while (p.S * p.NT < 2 * SPEC_NUM_CU && (p.steps + GEMM_WAVES * p.S * 2 - 1) / (GEMM_WAVES * p.S * 2) >= 2) p.S *= 2;
   p.spw = (p.steps + GEMM_WAVES * p.S - 1) / (GEMM_WAVES * p.S);
   p.Gs = slots / p.S;
   if (p.Gs < 1) p.Gs = 1;
-  if (p.Gs > p.NT / 2) p.Gs = p.NT / 2 > 0 ? p.NT / 2 : 1;   // at least one gate/up panel pair per workgroup
+  if (p.Gs > p.NT) p.Gs = p.NT;
   return p;
 }
 
-__device__ __forceinline__ void load_chunk(u32x4 (&a)[GEMM_SPW], const u32x4* __restrict__ wp, int nst) {
+// Loads / multiplies one chunk of 8 K-steps (steps CH*8 .. CH*8+7 of the wave's range) of one panel.
+__device__ __forceinline__ void load_chunk(u32x4 (&a)[8], const u32x4* __restrict__ wp, int first, int nst) {
 #pragma unroll
-  for (int j = 0; j < GEMM_SPW; ++j)
-    if (j < nst) a[j] = GEMM_LOAD(wp + (size_t)j * 64);
+  for (int j = 0; j < 8; ++j)
+    if (first + j < nst) a[j] = GEMM_LOAD(wp + (size_t)(first + j) * 64);
 }
 
-template <int MT>
-__device__ __forceinline__ void mma_chunk(f32x4 (&acc)[MT], const u32x4 (&a)[GEMM_SPW],
-                                          const bf16x8 (&b)[MT][GEMM_SPW], int nst) {
+template <int MT, int SPWMAX, int CH>
+__device__ __forceinline__ void mma_chunk(f32x4 (&acc)[MT], const u32x4 (&a)[8], const bf16x8 (&b)[MT][SPWMAX],
+                                          int nst) {
 #pragma unroll
-  for (int j = 0; j < GEMM_SPW; ++j)
-    if (j < nst) {
+  for (int j = 0; j < 8; ++j)
+    if (CH * 8 + j < nst) {
       bf16x8 av = __builtin_bit_cast(bf16x8, a[j]);
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, b[mt][j], acc[mt], 0, 0, 0);
+      for (int mt = 0; mt < MT; ++mt)
+        acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, b[mt][CH * 8 + j], acc[mt], 0, 0, 0);
     }
 }
 
-// Epilogue of one (row m, panel p, quad q) group: t holds the sums of columns 16 p + 4 q .. + 3 (t2: the same
-// columns of panel p + 1 for EPI_SILU).
-template <int EPI>
-__device__ __forceinline__ void epi_store(const GemmArgs& a, int m, int p, int q, f32x4 t, f32x4 t2, float& ss) {
-  const size_t n = (size_t)p * 16 + q * 4;
-  if (EPI == EPI_F32) {
-    *reinterpret_cast<f32x4*>(static_cast<float*>(a.out) + (size_t)m * a.N + n) = t;
-  } else if (EPI == EPI_RESID) {
-    f32x4* hp = reinterpret_cast<f32x4*>(static_cast<float*>(a.out) + (size_t)m * a.N + n);
-    f32x4 v = *hp;
-    v += t;
-    *hp = v;
-    ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
-  } else if (EPI == EPI_SILU) {
-    const size_t f = (size_t)(p >> 1) * 16 + q * 4;
-    bf16* dst = static_cast<bf16*>(a.out) + (size_t)m * (a.N >> 1) + f;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const float g = t[e];
-      dst[e] = __float2bfloat16(g / (1.0f + __expf(-g)) * t2[e]);
-    }
-  }
-}
-
-// TAG only names the instantiation (0 = target model, 1 = draft model, 2 = stand-alone call) so that profilers
-// list the two models' launches separately.  WPE = waves per SIMD the register budget is sized for: the 16-row
-// variant is held to 128 VGPRs (WPE 4) so that two workgroups share a CU: 16 waves per CU hide the HBM latency
-// far better than 8 (measured 6.9 vs 5.9 TB/s on the gate/up matrix), and the second slot can also go to the
-// other stream's kernel.
-template <int MT, int TAG, int WPE, int EPI, int PRO>
-__global__ __launch_bounds__(GEMM_THREADS, WPE) void gemm_kernel(const GemmArgs a) {
+// TAG only names the instantiation (0 = target model, 1 = draft model, 2 = stand-alone call) so
+// that profilers list the two models' launches separately.
+// WPE = waves per SIMD the register budget is sized for.  The 16-row variant is held to 128 VGPRs (WPE 4) so
+// that two workgroups share a CU: 16 waves per CU hide the HBM latency far better than 8 (measured 6.9 vs
+// 5.9 TB/s on the gate/up matrix), and the second slot can also go to the other stream's kernel.
+template <int MT, int SPWMAX, int TAG, int WPE>
+__global__ __launch_bounds__(GEMM_THREADS, WPE) void gemm_partial_kernel(const bf16* __restrict__ X,
+                                                                    const u32x4* __restrict__ Wp,
+                                                                    float* __restrict__ P, int M, int N, int K,
+                                                                    int NT, int steps, int S, int spw, int Gs) {
+  constexpr int NCH = SPWMAX / 8;            // chunks per panel
+  constexpr int UNITS = GEMM_RP * NCH;       // chunks per reduction round (even)
   constexpr int NBUF = (MT == 1) ? 2 : 1;    // LDS reduction buffers: two let a round end with a single barrier
   __shared__ f32x4 red[NBUF][GEMM_WAVES][GEMM_RP][MT][64];
-  __shared__ int s_last;
-  const int M = a.M, N = a.N, K = a.K, S = a.S, Gs = a.Gs;
   const int s = blockIdx.x % S;
   const int idx = blockIdx.x / S;
-  const int units = a.NT >> 1;               // panel ranges are cut at even panels (gate/up pairs stay together)
-  int p0 = 2 * (int)((long long)idx * units / Gs);
-  int p1 = 2 * (int)((long long)(idx + 1) * units / Gs);
-  if (idx == Gs - 1) p1 = a.NT;              // an odd panel count: the last range takes the odd one
+  const int p0 = (int)((long long)idx * NT / Gs);
+  const int p1 = (int)((long long)(idx + 1) * NT / Gs);
   const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int c = lane & 15, kb = lane >> 4;
-  const int step0 = (s * GEMM_WAVES + w) * a.spw;
-  int nst = a.steps - step0;
-  if (nst > a.spw) nst = a.spw;
+  const int step0 = (s * GEMM_WAVES + w) * spw;
+  int nst = steps - step0;
+  if (nst > spw) nst = spw;
   if (nst < 0) nst = 0;
 
   // activation fragments of this wave's K range, kept for the whole kernel
-  bf16x8 b[MT][GEMM_SPW];
+  bf16x8 b[MT][SPWMAX];
 #pragma unroll
-  for (int mt = 0; mt < MT; ++mt) {
-    const int m = mt * 16 + c;
-    float inv = 0.f;
-    if (PRO == PRO_NORM && m < M) inv = 1.0f / sqrtf(a.sumsq_in[m] / (float)K + a.eps);
+  for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-    for (int j = 0; j < GEMM_SPW; ++j) {
+    for (int j = 0; j < SPWMAX; ++j) {
+      const int m = mt * 16 + c;
       const int k = (step0 + j) * 32 + kb * 8;
       u32x4 v = {0u, 0u, 0u, 0u};
-      if (j < nst && m < M && k < K) {
-        if (PRO == PRO_BF16) {
-          v = *reinterpret_cast<const u32x4*>(static_cast<const bf16*>(a.X) + (size_t)m * K + k);
-        } else {
-          const float* hp = static_cast<const float*>(a.X) + (size_t)m * K + k;
-          const f32x4 h0 = *reinterpret_cast<const f32x4*>(hp), h1 = *reinterpret_cast<const f32x4*>(hp + 4);
-          const bf16x8 g = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(a.gain + k));
-          bf16x8 o;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            o[e] = (__bf16)(h0[e] * inv * (float)g[e]);
-            o[e + 4] = (__bf16)(h1[e] * inv * (float)g[e + 4]);
-          }
-          v = __builtin_bit_cast(u32x4, o);
-        }
-      }
+      if (j < nst && m < M && k < K) v = *reinterpret_cast<const u32x4*>(X + (size_t)m * K + k);
       b[mt][j] = __builtin_bit_cast(bf16x8, v);
     }
-  }
 
-  const u32x4* wbase = a.Wp + (size_t)step0 * 64 + lane;
-  const size_t pstride = (size_t)a.steps * 64;   // 16-byte units per panel
-  // Two-deep software pipeline over the panels: the chunks of panels q and q+1 are in flight; once a chunk is
-  // consumed its buffer is refilled with panel q+2.  The sequence runs on across reduction rounds, so the
-  // loads never drain at a round's barrier.
-  u32x4 av[2][GEMM_SPW];
+  const u32x4* wbase = Wp + (size_t)step0 * 64 + lane;
+  const size_t pstride = (size_t)steps * 64;   // 16-byte units per panel
+  // Two-deep software pipeline over the chunk sequence (panel-major, NCH chunks per panel): chunks q and
+  // q+1 are in flight; once chunk q is consumed its buffer is refilled with chunk q+2.  The sequence runs on
+  // across reduction rounds, so the loads never drain at a round's barrier.
+  u32x4 a[2][8];
 #pragma unroll
   for (int q = 0; q < 2; ++q)
-    if (p0 + q < p1) load_chunk(av[q], wbase + (size_t)(p0 + q) * pstride, nst);
+    if (p0 + q / NCH < p1) load_chunk(a[q], wbase + (size_t)(p0 + q / NCH) * pstride, (q % NCH) * 8, nst);
 
-  float ss = 0.f;
   int rb = 0;
   for (int pr = p0; pr < p1; pr += GEMM_RP) {
     f32x4 acc[GEMM_RP][MT];
@@ -165,9 +121,13 @@ __global__ __launch_bounds__(GEMM_THREADS, WPE) void gemm_kernel(const GemmArgs 
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) acc[rp][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int u = 0; u < GEMM_RP; ++u) {
-      if (pr + u < p1) mma_chunk<MT>(acc[u], av[u & 1], b, nst);
-      if (pr + u + 2 < p1) load_chunk(av[u & 1], wbase + (size_t)(pr + u + 2) * pstride, nst);
+    for (int u = 0; u < UNITS; ++u) {
+      if (pr + u / NCH < p1) {
+        if (u % NCH == 0) mma_chunk<MT, SPWMAX, 0>(acc[u / NCH], a[u & 1], b, nst);
+        else mma_chunk<MT, SPWMAX, (NCH > 1 ? 1 : 0)>(acc[u / NCH], a[u & 1], b, nst);
+      }
+      const int pn = pr + (u + 2) / NCH;
+      if (pn < p1) load_chunk(a[u & 1], wbase + (size_t)pn * pstride, ((u + 2) % NCH) * 8, nst);
     }
 
 #pragma unroll
@@ -179,21 +139,11 @@ __global__ __launch_bounds__(GEMM_THREADS, WPE) void gemm_kernel(const GemmArgs 
       const int l2 = item & 63, mt = (item >> 6) % MT, rp = item / (64 * MT);
       const int p = pr + rp;
       const int m = mt * 16 + (l2 & 15);
-      const bool pair = (EPI == EPI_SILU) && S == 1;   // gate and up sums are needed in one thread
-      if (pair && (rp & 1)) continue;
       if (p < p1 && m < M) {
-        f32x4 t = red[rb][0][rp][mt][l2], t2 = f32x4{0.f, 0.f, 0.f, 0.f};
+        f32x4 t = red[rb][0][rp][mt][l2];
 #pragma unroll
         for (int ww = 1; ww < GEMM_WAVES; ++ww) t += red[rb][ww][rp][mt][l2];
-        if (pair) {
-          t2 = red[rb][0][rp + 1][mt][l2];
-#pragma unroll
-          for (int ww = 1; ww < GEMM_WAVES; ++ww) t2 += red[rb][ww][rp + 1][mt][l2];
-        }
-        if (EPI != EPI_PARTIAL && S == 1)
-          epi_store<EPI>(a, m, p, l2 >> 4, t, t2, ss);
-        else
-          *reinterpret_cast<f32x4*>(a.P + ((size_t)s * M + m) * N + (size_t)p * 16 + (l2 >> 4) * 4) = t;
+        *reinterpret_cast<f32x4*>(P + ((size_t)s * M + m) * N + (size_t)p * 16 + (l2 >> 4) * 4) = t;
       }
     }
     // with two buffers the next round writes the other one, and nobody can reach the round after that
@@ -201,92 +151,24 @@ __global__ __launch_bounds__(GEMM_THREADS, WPE) void gemm_kernel(const GemmArgs 
     if (NBUF == 2) rb ^= 1;
     else __syncthreads();
   }
-  if (EPI == EPI_PARTIAL) return;
-
-  if (S > 1) {
-    // The last of the S workgroups of this panel range to get here adds the slices.  Release our partials,
-    // count arrivals, and (last one only) acquire the others' partials.
-    __threadfence();
-    __syncthreads();
-    if (threadIdx.x == 0) {
-      const int old = atomicAdd(&a.cnt[idx], 1);
-      s_last = (old == S - 1);
-      if (old == S - 1) a.cnt[idx] = 0;   // ready for the next launch
-    }
-    __syncthreads();
-    if (!s_last) return;
-    __threadfence();
-    const int step = (EPI == EPI_SILU) ? 2 : 1;
-    for (int item = threadIdx.x; item < (p1 - p0) * MT * 64; item += GEMM_THREADS) {
-      const int l2 = item & 63, mt = (item >> 6) % MT, pp = item / (64 * MT);
-      if (step == 2 && (pp & 1)) continue;
-      const int p = p0 + pp;
-      const int m = mt * 16 + (l2 & 15);
-      if (m < M) {
-        const size_t off = (size_t)m * N + (size_t)p * 16 + (l2 >> 4) * 4;
-        f32x4 t = f32x4{0.f, 0.f, 0.f, 0.f}, t2 = f32x4{0.f, 0.f, 0.f, 0.f};
-        for (int sl = 0; sl < S; ++sl) {
-          const float* ps = a.P + (size_t)sl * M * N + off;
-          t += *reinterpret_cast<const f32x4*>(ps);
-          if (step == 2) t2 += *reinterpret_cast<const f32x4*>(ps + 16);
-        }
-        epi_store<EPI>(a, m, p, l2 >> 4, t, t2, ss);
-      }
-    }
-  }
-
-  if (EPI == EPI_RESID) {
-    // sum of squares of the updated rows: per workgroup in a fixed order, then across workgroups by the last
-    // one to finish (again a counter, no waiting)
-    float* sred = reinterpret_cast<float*>(&red[0][0][0][0][0]);
-    __syncthreads();
-    sred[threadIdx.x] = ss;
-    __syncthreads();
-    if (threadIdx.x < 16 * MT) {
-      const int cc = threadIdx.x & 15, mt = threadIdx.x >> 4;
-      float tot = 0.f;
-      for (int t = 0; t < GEMM_THREADS; ++t)
-        if ((t & 15) == cc && ((t >> 6) % MT) == mt) tot += sred[t];
-      a.slots[(size_t)idx * SPEC_MAX_TOKENS + threadIdx.x] = tot;
-    }
-    __threadfence();
-    __syncthreads();
-    if (threadIdx.x == 0) {
-      const int old = atomicAdd(a.done, 1);
-      s_last = (old == Gs - 1);
-      if (old == Gs - 1) a.done[0] = 0;
-    }
-    __syncthreads();
-    if (!s_last) return;
-    __threadfence();
-    if (threadIdx.x < M) {
-      float tot = 0.f;
-      for (int i = 0; i < Gs; ++i) tot += a.slots[(size_t)i * SPEC_MAX_TOKENS + threadIdx.x];
-      a.sumsq_out[threadIdx.x] = tot;
-    }
-  }
 }
 
-template <int TAG, int EPI, int PRO>
-static void launch_variant(const GemmPlan& p, const GemmArgs& a, hipStream_t st) {
+template <int TAG>
+static void launch_tagged(const GemmPlan& p, const bf16* x, const void* wp, float* partials, hipStream_t st) {
   dim3 grid(p.Gs * p.S), block(GEMM_THREADS);
   if (p.MT == 1)
-    gemm_kernel<1, TAG, 4, EPI, PRO><<<grid, block, 0, st>>>(a);
+    gemm_partial_kernel<1, 8, TAG, 4><<<grid, block, 0, st>>>(x, (const u32x4*)wp, partials, p.M, p.N, p.K, p.NT,
+                                                               p.steps, p.S, p.spw, p.Gs);
   else
-    gemm_kernel<2, TAG, 2, EPI, PRO><<<grid, block, 0, st>>>(a);
+    gemm_partial_kernel<2, 8, TAG, 2><<<grid, block, 0, st>>>(x, (const u32x4*)wp, partials, p.M, p.N, p.K, p.NT,
+                                                               p.steps, p.S, p.spw, p.Gs);
 }
 
-hipError_t launch_gemm(const GemmPlan& p, GemmArgs a, int epi, int pro, int tag, hipStream_t st) {
-  a.M = p.M; a.N = p.N; a.K = p.K; a.NT = p.NT; a.steps = p.steps; a.S = p.S; a.spw = p.spw; a.Gs = p.Gs;
-  const int key = epi * 2 + pro;
-  if (tag == 2 && key == EPI_PARTIAL * 2 + PRO_BF16) launch_variant<2, EPI_PARTIAL, PRO_BF16>(p, a, st);
-#define GEMM_CASE(T, E, Pm) else if (tag == T && key == E * 2 + Pm) launch_variant<T, E, Pm>(p, a, st);
-  GEMM_CASE(0, EPI_PARTIAL, PRO_NORM) GEMM_CASE(1, EPI_PARTIAL, PRO_NORM)
-  GEMM_CASE(0, EPI_RESID, PRO_BF16) GEMM_CASE(1, EPI_RESID, PRO_BF16)
-  GEMM_CASE(0, EPI_SILU, PRO_NORM) GEMM_CASE(1, EPI_SILU, PRO_NORM)
-  GEMM_CASE(0, EPI_F32, PRO_NORM) GEMM_CASE(1, EPI_F32, PRO_NORM)
-#undef GEMM_CASE
-  else return hipErrorInvalidValue;
+hipError_t launch_gemm_partials(const GemmPlan& p, const bf16* x, const void* wp, float* partials, hipStream_t st,
+                                int tag) {
+  if (tag == 0) launch_tagged<0>(p, x, wp, partials, st);
+  else if (tag == 1) launch_tagged<1>(p, x, wp, partials, st);
+  else launch_tagged<2>(p, x, wp, partials, st);
   return hipGetLastError();
 }
 

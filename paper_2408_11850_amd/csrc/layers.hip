@@ -1,6 +1,6 @@
-// Small per-token kernels around the projections (gfx950): token gather, embedding, RoPE + KV append.
-// (RMSNorm, the residual adds and SiLU*mul are fused into the projection kernel.)  The RoPE kernel reads the
-// fp32 K-slice partials of the QKV projection and adds the slices in ascending order.
+// Small per-token kernels between the projections (gfx950): token gather, embedding,
+// residual add + RMSNorm, RoPE + KV append, SiLU*mul.  All of them read the fp32 K-slice
+// partials of the preceding projection and add the slices in ascending order.
 #include "spec_internal.h"
 
 __global__ void gather_tokens_kernel(int* tok_out, const int* ring, TokenSrc src) {
@@ -31,31 +31,92 @@ hipError_t launch_set_pages(int* block_table, PageUpdate u, hipStream_t st) {
   return hipGetLastError();
 }
 
-// h[m][:] = float(E[tok[m]][:]) and sumsq[m] = sum_i h[m][i]^2 (added in a fixed order); an id outside the
-// vocabulary reads row 0 (ids are validated on the host)
-__global__ __launch_bounds__(256) void embed_kernel(float* __restrict__ h, float* __restrict__ sumsq,
-                                                    const bf16* __restrict__ E, const int* __restrict__ tok, int d,
-                                                    int vocab) {
-  __shared__ float sh[4];
+// h[m][:] = float(E[tok[m]][:]); an id outside the vocabulary reads row 0 (ids are validated on the host)
+__global__ void embed_kernel(float* __restrict__ h, const bf16* __restrict__ E, const int* __restrict__ tok, int d,
+                             int vocab) {
   const int m = blockIdx.x;
   int t = tok[m];
   if (t < 0 || t >= vocab) t = 0;
   const bf16* row = E + (size_t)t * d;
+  for (int i = threadIdx.x; i < d; i += blockDim.x) h[(size_t)m * d + i] = __bfloat162float(row[i]);
+}
+hipError_t launch_embed(float* h, const bf16* embed, const int* tok, int M, int d, int vocab, hipStream_t st) {
+  embed_kernel<<<M, 256, 0, st>>>(h, embed, tok, d, vocab);
+  return hipGetLastError();
+}
+
+__device__ __forceinline__ float block_sum(float v, float* sh) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  const int w = threadIdx.x >> 6;
+  if ((threadIdx.x & 63) == 0) sh[w] = v;
+  __syncthreads();
+  float t = 0.f;
+  const int nw = blockDim.x >> 6;
+  for (int i = 0; i < nw; ++i) t += sh[i];
+  __syncthreads();
+  return t;
+}
+
+// h[m] += sum_s P[s][m] ; a[m] = h[m] * rsqrt(mean(h[m]^2) + eps) * gain.
+// One workgroup of 1024 threads per row; a thread keeps its (at most 4) float4 pieces of the row in
+// registers, and the S slice loads of a piece are independent, so the row is read in a few round trips.
+#define ADDNORM_THREADS 1024
+#define ADDNORM_PIECES 4      // d_model <= 4 * 4 * 1024
+__global__ __launch_bounds__(ADDNORM_THREADS) void addnorm_kernel(float* __restrict__ h, const float* __restrict__ P,
+                                                                  int S, const bf16* __restrict__ gain,
+                                                                  bf16* __restrict__ a, int M, int d, float eps) {
+  __shared__ float sh[ADDNORM_THREADS / 64];
+  const int m = blockIdx.x;
+  const int d4 = d >> 2;
+  f32x4* hr = reinterpret_cast<f32x4*>(h + (size_t)m * d);
+  const f32x4* P4 = reinterpret_cast<const f32x4*>(P);
+  f32x4 v[ADDNORM_PIECES];
   float ss = 0.f;
-  for (int i = threadIdx.x; i < d; i += 256) {
-    const float v = __bfloat162float(row[i]);
-    h[(size_t)m * d + i] = v;
-    ss += v * v;
+#pragma unroll
+  for (int it = 0; it < ADDNORM_PIECES; ++it) {
+    const int i = threadIdx.x + it * ADDNORM_THREADS;
+    v[it] = f32x4{0.f, 0.f, 0.f, 0.f};
+    if (i < d4) {
+      f32x4 t = hr[i];
+      if (P) {
+        int s = 0;
+        for (; s + 4 <= S; s += 4) {   // four independent loads in flight, added in ascending slice order
+          const f32x4 p0 = P4[((size_t)(s + 0) * M + m) * d4 + i], p1 = P4[((size_t)(s + 1) * M + m) * d4 + i];
+          const f32x4 p2 = P4[((size_t)(s + 2) * M + m) * d4 + i], p3 = P4[((size_t)(s + 3) * M + m) * d4 + i];
+          t += p0; t += p1; t += p2; t += p3;
+        }
+        for (; s < S; ++s) t += P4[((size_t)s * M + m) * d4 + i];
+      }
+      hr[i] = t;
+      v[it] = t;
+      ss += t.x * t.x + t.y * t.y + t.z * t.z + t.w * t.w;
+    }
   }
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
   if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = ss;
   __syncthreads();
-  if (threadIdx.x == 0) sumsq[m] = sh[0] + sh[1] + sh[2] + sh[3];
+  float tot = 0.f;
+#pragma unroll
+  for (int i = 0; i < ADDNORM_THREADS / 64; ++i) tot += sh[i];
+  const float inv = 1.0f / sqrtf(tot / (float)d + eps);
+#pragma unroll
+  for (int it = 0; it < ADDNORM_PIECES; ++it) {
+    const int i = threadIdx.x + it * ADDNORM_THREADS;
+    if (i < d4) {
+      const bf16* g = gain + (size_t)i * 4;
+      bf16* dst = a + (size_t)m * d + (size_t)i * 4;
+      dst[0] = __float2bfloat16(v[it].x * inv * __bfloat162float(g[0]));
+      dst[1] = __float2bfloat16(v[it].y * inv * __bfloat162float(g[1]));
+      dst[2] = __float2bfloat16(v[it].z * inv * __bfloat162float(g[2]));
+      dst[3] = __float2bfloat16(v[it].w * inv * __bfloat162float(g[3]));
+    }
+  }
 }
-hipError_t launch_embed(float* h, float* sumsq, const bf16* embed, const int* tok, int M, int d, int vocab,
-                        hipStream_t st) {
-  embed_kernel<<<M, 256, 0, st>>>(h, sumsq, embed, tok, d, vocab);
+hipError_t launch_addnorm(float* h, const float* partials, int S, const bf16* gain, bf16* a, int M, int d, float eps,
+                          hipStream_t st) {
+  addnorm_kernel<<<M, ADDNORM_THREADS, 0, st>>>(h, partials, S, gain, a, M, d, eps);
   return hipGetLastError();
 }
 
@@ -111,5 +172,26 @@ hipError_t launch_rope_append(const float* partials, int S, bf16* q, bf16* pool,
                               const int* len_ptr, KvGeom g, int layer, int M, int Hq, float theta, hipStream_t st) {
   dim3 grid(M, Hq + 2 * g.n_kv_heads), block(64);
   rope_append_kernel<<<grid, block, 0, st>>>(partials, S, q, pool, block_table, len_ptr, g, layer, M, Hq, theta);
+  return hipGetLastError();
+}
+
+// z[m][f] = silu(gate) * up, gate/up panels interleaved in the fused projection output (width 2F)
+__global__ void silu_mul_kernel(const float* __restrict__ P, int S, bf16* __restrict__ z, int M, int F) {
+  const int m = blockIdx.y;
+  const int f = blockIdx.x * blockDim.x + threadIdx.x;
+  if (f >= F) return;
+  const int gc = (f >> 4) * 32 + (f & 15);
+  float gv = 0.f, uv = 0.f;
+  for (int s = 0; s < S; ++s) {
+    const float* row = P + ((size_t)s * M + m) * (2 * (size_t)F);
+    gv += row[gc];
+    uv += row[gc + 16];
+  }
+  const float sg = gv / (1.0f + __expf(-gv));
+  z[(size_t)m * F + f] = __float2bfloat16(sg * uv);
+}
+hipError_t launch_silu_mul(const float* partials, int S, bf16* z, int M, int F, hipStream_t st) {
+  dim3 grid((F + 255) / 256, M), block(256);
+  silu_mul_kernel<<<grid, block, 0, st>>>(partials, S, z, M, F);
   return hipGetLastError();
 }

@@ -52,8 +52,6 @@ struct ModelRt {
   float* h = nullptr;
   bf16 *a = nullptr, *qbuf = nullptr, *attn_out = nullptr, *z = nullptr;
   float *partials = nullptr, *opart = nullptr, *mlpart = nullptr, *logits = nullptr;
-  int* gemm_cnt = nullptr;        // arrival counters of the projection kernel (zero between launches) + done counter
-  float *gemm_slots = nullptr, *sumsq = nullptr;
   long long n_forwards = 0;
   int split_tokens = 0;           // context length the attention split count is sized for (fixed per context)
   // captured forwards, keyed [tokens][logit mode 0/1/2][projection workgroups per CU]
@@ -168,11 +166,6 @@ int init_model(ModelRt& m, const spec_model_desc& d, const spec_weights& w, cons
   if ((rc = dev_alloc(&m.opart, aw))) return rc;
   m.mlpart = m.opart + (aw / (d.head_dim + 2)) * d.head_dim;
   if ((rc = dev_alloc(&m.logits, (size_t)MX * d.vocab))) return rc;
-  const size_t n_cnt = 2 * SPEC_NUM_CU + 16;
-  if ((rc = dev_alloc(&m.gemm_cnt, n_cnt))) return rc;
-  HIPCHK(hipMemset(m.gemm_cnt, 0, n_cnt * sizeof(int)));
-  if ((rc = dev_alloc(&m.gemm_slots, (size_t)2 * SPEC_NUM_CU * SPEC_MAX_TOKENS))) return rc;
-  if ((rc = dev_alloc(&m.sumsq, (size_t)SPEC_MAX_TOKENS))) return rc;
   return SPEC_OK;
 }
 
@@ -185,7 +178,7 @@ void free_model(ModelRt& m) {
           g = nullptr;
         }
   void* ptrs[] = {m.pool, m.block_table_dev, m.len_dev, m.tok_in, m.h, m.a, m.qbuf, m.attn_out, m.z, m.partials,
-                  m.opart, m.logits, m.gemm_cnt, m.gemm_slots, m.sumsq};
+                  m.opart, m.logits};
   for (void* p : ptrs)
     if (p) (void)hipFree(p);
 }
@@ -235,70 +228,52 @@ int prof_end(spec_ctx* c, hipStream_t st) {
   return SPEC_OK;
 }
 
-GemmArgs gemm_args(ModelRt& m) {
-  GemmArgs a;
-  memset(&a, 0, sizeof(a));
-  a.sumsq_in = m.sumsq;
-  a.eps = m.d.rms_eps;
-  a.P = m.partials;
-  a.cnt = m.gemm_cnt;
-  a.done = m.gemm_cnt + 2 * SPEC_NUM_CU;
-  a.slots = m.gemm_slots;
-  a.sumsq_out = m.sumsq;
-  return a;
-}
-
-// One projection of the forward.  x: bf16 activations (PRO_BF16) or the fp32 residual stream (PRO_NORM, with
-// `gain`); out: see GemmArgs.
-int run_gemm(spec_ctx* c, int which, ModelRt& m, const GemmPlan& p, GemmArgs a, const void* x, const void* gain,
-             const void* w, void* out, int epi, int pro) {
-  a.X = x;
-  a.gain = (const bf16*)gain;
-  a.Wp = (const u32x4*)w;
-  a.out = out;
+int run_gemm(spec_ctx* c, int which, ModelRt& m, int M, int N, int K, const bf16* x, const void* w, GemmPlan* plan_out) {
+  GemmPlan p = gemm_plan(M, N, K, c->wgs);
   const bool prof = (c->profile_flags & 1) && which == SPEC_TARGET;
   int rc;
   if (prof && (rc = prof_begin(c, m.stream, (double)p.weight_bytes()))) return rc;
-  HIPCHK(launch_gemm(p, a, epi, pro, which, m.stream));
+  HIPCHK(launch_gemm_partials(p, x, w, m.partials, m.stream, which));
   if (prof && (rc = prof_end(c, m.stream))) return rc;
+  *plan_out = p;
   return SPEC_OK;
 }
 
 // The kernel chain of one forward over the M tokens in m.tok_in.  Nothing here depends on host state other
 // than M, logit_rows and the launch mode: positions come from *len_dev, pages from the device block table,
-// so the chain can be captured once into a HIP graph and replayed.  Seven launches per layer: QKV projection
-// (RMSNorm applied while loading h), RoPE + KV append, attention split and merge, O projection (+ residual),
-// gate/up projection (RMSNorm on load, SiLU*mul on store), down projection (+ residual).
+// so the chain can be captured once into a HIP graph and replayed.
 int enqueue_forward(spec_ctx* c, int which, int M, int logit_rows) {
   ModelRt& m = c->m[which];
   const spec_model_desc& d = m.d;
   hipStream_t st = m.stream;
   int rc;
-  HIPCHK(launch_embed(m.h, m.sumsq, (const bf16*)m.tok_embed, m.tok_in, M, d.d_model, d.vocab, st));
+  HIPCHK(launch_embed(m.h, (const bf16*)m.tok_embed, m.tok_in, M, d.d_model, d.vocab, st));
   const int qkvN = (d.n_heads + 2 * d.n_kv_heads) * d.head_dim;
   const int HD = d.n_heads * d.head_dim;
-  const GemmPlan p_qkv = gemm_plan(M, qkvN, d.d_model, c->wgs), p_o = gemm_plan(M, d.d_model, HD, c->wgs);
-  const GemmPlan p_gu = gemm_plan(M, 2 * d.d_ffn, d.d_model, c->wgs), p_dn = gemm_plan(M, d.d_model, d.d_ffn, c->wgs);
-  const GemmArgs a0 = gemm_args(m);
+  GemmPlan p;
+  const float* prev = nullptr;
+  int prevS = 0;
   for (int l = 0; l < d.n_layers; ++l) {
-    if ((rc = run_gemm(c, which, m, p_qkv, a0, m.h, m.attn_norm[l], m.wqkv[l], nullptr, EPI_PARTIAL, PRO_NORM))) return rc;
-    HIPCHK(launch_rope_append(m.partials, p_qkv.S, m.qbuf, m.pool, m.block_table_dev, m.len_dev, m.geom, l, M,
-                              d.n_heads, d.rope_theta, st));
+    HIPCHK(launch_addnorm(m.h, prev, prevS, (const bf16*)m.attn_norm[l], m.a, M, d.d_model, d.rms_eps, st));
+    if ((rc = run_gemm(c, which, m, M, qkvN, d.d_model, m.a, m.wqkv[l], &p))) return rc;
+    HIPCHK(launch_rope_append(m.partials, p.S, m.qbuf, m.pool, m.block_table_dev, m.len_dev, m.geom, l, M, d.n_heads,
+                              d.rope_theta, st));
     HIPCHK(launch_attention(m.qbuf, m.pool, m.block_table_dev, m.len_dev, m.geom, l, M, d.n_heads, m.split_tokens,
                             m.opart, m.mlpart, m.attn_out, st));
-    if ((rc = run_gemm(c, which, m, p_o, a0, m.attn_out, nullptr, m.wo[l], m.h, EPI_RESID, PRO_BF16))) return rc;
-    if ((rc = run_gemm(c, which, m, p_gu, a0, m.h, m.ffn_norm[l], m.wgu[l], m.z, EPI_SILU, PRO_NORM))) return rc;
-    if ((rc = run_gemm(c, which, m, p_dn, a0, m.z, nullptr, m.wdown[l], m.h, EPI_RESID, PRO_BF16))) return rc;
+    if ((rc = run_gemm(c, which, m, M, d.d_model, HD, m.attn_out, m.wo[l], &p))) return rc;
+    HIPCHK(launch_addnorm(m.h, m.partials, p.S, (const bf16*)m.ffn_norm[l], m.a, M, d.d_model, d.rms_eps, st));
+    if ((rc = run_gemm(c, which, m, M, 2 * d.d_ffn, d.d_model, m.a, m.wgu[l], &p))) return rc;
+    HIPCHK(launch_silu_mul(m.partials, p.S, m.z, M, d.d_ffn, st));
+    if ((rc = run_gemm(c, which, m, M, d.d_model, d.d_ffn, m.z, m.wdown[l], &p))) return rc;
+    prev = m.partials;
+    prevS = p.S;
   }
   if (logit_rows > 0) {
-    // the LM head of the last `rows` tokens: shift the row-indexed inputs
+    HIPCHK(launch_addnorm(m.h, prev, prevS, (const bf16*)m.final_norm, m.a, M, d.d_model, d.rms_eps, st));
     const int rows = logit_rows >= M ? M : 1;
-    const size_t skip = (size_t)(M - rows);
-    GemmArgs a = a0;
-    a.sumsq_in = m.sumsq + skip;
-    if ((rc = run_gemm(c, which, m, gemm_plan(rows, d.vocab, d.d_model, c->wgs), a, m.h + skip * d.d_model,
-                       m.final_norm, m.lm_head, m.logits, EPI_F32, PRO_NORM)))
-      return rc;
+    const bf16* x = m.a + (size_t)(M - rows) * d.d_model;
+    if ((rc = run_gemm(c, which, m, rows, d.vocab, d.d_model, x, m.lm_head, &p))) return rc;
+    HIPCHK(launch_reduce_partials(m.logits, m.partials, p.S, (size_t)rows * d.vocab, st));
   }
   HIPCHK(launch_add_int(m.len_dev, M, st));
   return SPEC_OK;
@@ -775,12 +750,7 @@ extern "C" int spec_gemm_partials(const void* x, const void* w, int M, int N, in
   int rc = check_gemm_args(M, N, K);
   if (rc) return rc;
   GemmPlan p = gemm_plan(M, N, K);
-  GemmArgs a;
-  memset(&a, 0, sizeof(a));
-  a.X = x;
-  a.Wp = (const u32x4*)w;
-  a.P = (float*)work;
-  HIPCHK(launch_gemm(p, a, EPI_PARTIAL, PRO_BF16, 2, (hipStream_t)stream));
+  HIPCHK(launch_gemm_partials(p, (const bf16*)x, w, (float*)work, (hipStream_t)stream, 2));
   return SPEC_OK;
 }
 extern "C" int spec_gemm(float* y, const void* x, const void* w, int M, int N, int K, void* work, void* stream) {

@@ -36,24 +36,8 @@ struct GemmPlan {
 // wgs_per_cu: 2 = fill both workgroup slots of every CU (a stream running alone), 1 = leave one slot to
 // the other stream's kernels.  The K split (S, spw) does not depend on it.
 GemmPlan gemm_plan(int M, int N, int K, int wgs_per_cu = 2);
-// What a projection launch does with its inputs (PRO_*) and sums (EPI_*); see gemm.hip.
-enum { EPI_PARTIAL = 0, EPI_F32 = 1, EPI_RESID = 2, EPI_SILU = 3 };
-enum { PRO_BF16 = 0, PRO_NORM = 1 };
-struct GemmArgs {
-  const void* X;          // PRO_BF16: bf16 [M][K];  PRO_NORM: fp32 residual stream h [M][K]
-  const bf16* gain;       // PRO_NORM: norm gains [K]
-  const float* sumsq_in;  // PRO_NORM: sum_k h[m][k]^2 per row
-  float eps;              // PRO_NORM
-  const u32x4* Wp;        // packed weights
-  float* P;               // K-slice partials [S][M][N] (EPI_PARTIAL always; other epilogues when S > 1)
-  void* out;              // EPI_F32: float y[M][N]; EPI_RESID: float h[M][N] (updated in place); EPI_SILU: bf16 z[M][N/2]
-  int* cnt;               // one arrival counter per panel range, zero between launches
-  int* done;              // EPI_RESID: arrival counter of the finished panel ranges, zero between launches
-  float* slots;           // EPI_RESID: per panel range and row, the range's share of sum h^2
-  float* sumsq_out;       // EPI_RESID: sum_n h[m][n]^2 per row
-  int M, N, K, NT, steps, S, spw, Gs;   // filled from the plan
-};
-hipError_t launch_gemm(const GemmPlan& p, GemmArgs a, int epi, int pro, int tag, hipStream_t st);
+hipError_t launch_gemm_partials(const GemmPlan& p, const bf16* x, const void* wp, float* partials, hipStream_t st,
+                                int tag);
 hipError_t launch_reduce_partials(float* y, const float* partials, int S, size_t n, hipStream_t st);
 hipError_t launch_pack_weight(void* dst, const void* src, int N, int K, int panel_start, int panel_step, hipStream_t st);
 hipError_t launch_read_probe(const void* src, size_t bytes, void* out, hipStream_t st);
@@ -86,15 +70,17 @@ hipError_t launch_gather_tokens(int* tok_out, const int* ring, TokenSrc src, hip
 hipError_t launch_set_int(int* dst, int value, hipStream_t st);
 hipError_t launch_add_int(int* dst, int delta, hipStream_t st);
 hipError_t launch_set_pages(int* block_table, PageUpdate u, hipStream_t st);
-// h[m] = E[tok[m]] (fp32) and sumsq[m] = sum h[m]^2
-hipError_t launch_embed(float* h, float* sumsq, const bf16* embed, const int* tok, int M, int d, int vocab,
-                        hipStream_t st);
+hipError_t launch_embed(float* h, const bf16* embed, const int* tok, int M, int d, int vocab, hipStream_t st);
+// h += sum_s partials[s] (if partials), a = rmsnorm(h) * gain
+hipError_t launch_addnorm(float* h, const float* partials, int S, const bf16* gain, bf16* a, int M, int d,
+                          float eps, hipStream_t st);
 hipError_t launch_rope_append(const float* partials, int S, bf16* q, bf16* pool, const int* block_table,
                               const int* len_ptr, KvGeom g, int layer, int M, int Hq, float theta, hipStream_t st);
 hipError_t launch_attention(const bf16* q, const bf16* pool, const int* block_table, const int* len_ptr, KvGeom g,
                             int layer, int M, int Hq, int split_tokens, float* opart, float* mlpart, bf16* out,
                             hipStream_t st);
 size_t attention_workspace_floats(int Hq, int Hkv, int dh, int max_seq);
+hipError_t launch_silu_mul(const float* partials, int S, bf16* z, int M, int F, hipStream_t st);
 
 // sampling / acceptance
 struct AcceptArgs {
