@@ -35,6 +35,8 @@ def parse():
     ap.add_argument("--depth", type=int, default=0, help="truncate the target to this many layers (experiments)")
     ap.add_argument("--draft-depth", type=int, default=0)
     ap.add_argument("--wgs", type=int, default=-1, help="projection workgroups per CU: -1 auto, 1, 2")
+    ap.add_argument("--sweep", action="store_true",
+                    help="instead of the benchmark line: tokens/s of PEARL and SD over window sizes and acceptance rates")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
     ap.add_argument("--no-side", action="store_true", help="skip AR / SD / forced-acceptance side runs")
     return ap.parse_args()
@@ -119,6 +121,41 @@ def cpu_baseline(cfg, gamma, device):
             "target_forward_s": full_t, "draft_forward_s": full_d}
 
 
+def sweep(args, cfg, ctx, amd, synth, sync, n0, tp, tq, log):
+    """Window-size and co-location study (the analogue of the paper's gamma tables on one GPU): tokens/s of
+    PEARL with one or two projection workgroups per CU and of vanilla SD, for gamma in a range, with the
+    pair's own acceptance decisions and with forced Bernoulli(alpha) decisions."""
+    steps = max(8, args.steps // 4)
+    rows = []
+
+    def run(algo, g, wgs, alpha):
+        ctx.rewind(n0)
+        ctx.set_option(amd.SPEC_OPT_GEMM_WGS_PER_CU, wgs)
+        u = synth.make_uniforms(steps + 3, g, cfg.seed_uniform)
+        fb = None
+        if alpha is not None:
+            fb = (synth.uniform_array((steps + 3) * (g + 1), 5, 7).view(steps + 3, g + 1).numpy() < alpha)
+        ctx.generate(algo, g, 1 << 20, u, force_bits=fb, max_steps=2)
+        sync(); t0 = time.perf_counter()
+        _, s = ctx.generate(algo, g, 1 << 20, u, force_bits=fb, max_steps=steps)
+        sync(); dt = time.perf_counter() - t0
+        return s["committed"] / dt, s["committed"] / s["steps"], dt / s["steps"] * 1e3
+
+    ar = run(amd.ALGO_AR, 1, 2, None)
+    log(f"[sweep] AR: {ar[0]:.2f} tok/s, {ar[2]:.2f} ms/step; c = {tp / tq:.2f}")
+    for alpha in (None, 0.7, 0.9):
+        for g in (2, 3, 4, 6, 8, 10, 12):
+            r = {"alpha": "pair" if alpha is None else alpha, "gamma": g}
+            for name, algo, wgs in (("pearl_1wg", amd.ALGO_PEARL, 1), ("pearl_2wg", amd.ALGO_PEARL, 2),
+                                    ("sd", amd.ALGO_SD, 2)):
+                tps, tpstep, ms = run(algo, g, wgs, alpha)
+                r[name] = {"tokens_per_s": round(tps, 2), "tokens_per_step": round(tpstep, 3), "step_ms": round(ms, 2)}
+            rows.append(r)
+            log(f"[sweep] {json.dumps(r)}")
+    print(json.dumps({"workload": cfg.name, "n_prompt": n0, "steps_per_point": steps, "c": tp / tq,
+                      "ar_tokens_per_s": ar[0], "rows": rows}))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -155,6 +192,11 @@ def main():
     log(f"[bench] target fwd {tp * 1e3:.2f} ms, draft fwd {tq * 1e3:.2f} ms, c = {tp / tq:.2f}, gamma = {gamma}")
     ctx.rewind(n0)
 
+    if args.sweep:
+        sweep(args, cfg, ctx, amd, synth, sync, n0, tp, tq, log)
+        ctx.close()
+        return
+
     # ---- each pass alone: bytes / time ---------------------------------------------------------
     def alone(fn, n):
         fn(); sync()
@@ -163,6 +205,13 @@ def main():
 
     t_v1 = alone(lambda: ctx.verify([1]), 6); ctx.rewind(n0)
     t_vg = alone(lambda: ctx.verify(list(range(1, gamma + 1))), 6); ctx.rewind(n0)
+    # the dominant kernel with the stream to itself: HIP events around every target projection of 3 forwards
+    ctx.set_profile(1); ctx.profile_read()
+    for _ in range(3):
+        ctx.verify(list(range(1, gamma + 1)))
+    ms_a, n_a, bytes_a = ctx.profile_read()
+    ctx.set_profile(0); ctx.rewind(n0)
+    gemm_alone = bytes_a / max(ms_a, 1e-9) / 1e6
 
     def draft_chain():
         ctx.draft_step(0.5)
@@ -247,10 +296,14 @@ def main():
                                f"{cfg.draft.n_layers}L d={cfg.draft.d_model}, V={cfg.target.vocab}, batch 1, prompt "
                                f"{cfg.n_prompt}, temperature {cfg.temperature}, gamma {gamma} (c={tp / tq:.2f})",
                    "gamma": gamma, "c": tp / tq, "n_prompt": cfg.n_prompt, "two_streams": True},
-        "roofline": {"bound": "hbm", "kernel": "gemm_partial_kernel<1,16,0> (target projections)",
+        "roofline": {"bound": "hbm", "kernel": "gemm_partial_kernel<1, 8, 0, 4> (target projections)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": traffic, "launches": int(n_gemm), "avg_launch_us": ms_gemm / max(n_gemm, 1) * 1e3,
-                     "avg_bytes_per_launch": bytes_gemm / max(n_gemm, 1), "read_ceiling_GBps": read_ceiling},
+                     "avg_bytes_per_launch": bytes_gemm / max(n_gemm, 1), "read_ceiling_GBps": read_ceiling,
+                     "note": "achieved = weight bytes / HIP-event time of this kernel's launches inside the timed PEARL "
+                             "steps, where it shares HBM with the draft stream; alone_* = same kernel, stream to itself",
+                     "alone_achieved": gemm_alone, "alone_frac": gemm_alone / HBM_PEAK_GBS,
+                     "alone_avg_launch_us": ms_a / max(n_a, 1) * 1e3},
         "pearl": pearl, "alone": alone_stats, "side": side,
         "setup_s": {"build": t_build, "prefill": t_prefill},
     }

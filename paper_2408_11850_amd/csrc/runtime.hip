@@ -650,7 +650,9 @@ extern "C" int spec_generate(spec_ctx* c, int algo, int gamma, int n_generate, i
   if (!c->prefilled) FAIL(SPEC_E_STATE, "spec_prefill has not run");
   const int g1 = gamma + 1;
   const int wgs_before = c->wgs;
-  if (c->wgs_opt < 0) c->wgs = ((algo == 2) && (c->m[0].stream != c->m[1].stream)) ? SPEC_PEARL_WGS_PER_CU : 2;
+  // while the two streams overlap, one projection workgroup per CU and stream is better from gamma 6 on (long draft chains),
+  // two per CU below that (measured on the 70B/7B-shape pair)
+  if (c->wgs_opt < 0) c->wgs = ((algo == 2) && (c->m[0].stream != c->m[1].stream) && gamma >= 6) ? SPEC_PEARL_WGS_PER_CU : 2;
   int mode = c->mode;
   int produced = 0, rc = 0;
   long long steps = 0, accepted = 0, tested = 0, post_steps = 0;
