@@ -10,7 +10,7 @@ from tests.util import bf16_pair, gpu_available, oracle_model
 pytestmark = [pytest.mark.gpu, pytest.mark.skipif(not gpu_available(), reason="needs a GPU")]
 
 LOGIT_TOL = 2e-2      # max |GPU - oracle| logit error, relative to the row's logit range (bf16 path vs fp32)
-DRAW_MARGIN_TOL = 0.02  # a draw may differ from the oracle's only if u lies this close to a CDF edge
+DRAW_MARGIN_TOL = 5e-3  # a draw may differ from the oracle's only if u lies this close to a CDF edge
 
 
 def _setup(cfg, gamma_max=8, temperature=1.0, extra_seq=0):

@@ -15,7 +15,8 @@ from tests.util import NpUniforms, bf16_pair, gpu_available, oracle_model
 
 pytestmark = [pytest.mark.gpu, pytest.mark.skipif(not gpu_available(), reason="needs a GPU")]
 
-MARGIN_TOL = 0.25      # a split is tolerated only on a step whose oracle margin is below this
+MARGIN_TOL = 5e-3     # a split is tolerated only on a step whose smallest oracle decision margin is below this
+#                     (observed splits: margins <= 4e-4; logit error 3e-3 of the range shifts a CDF edge by about 1e-3)
 
 
 def _pair(cfg):
@@ -102,6 +103,7 @@ def test_sampled_loops_follow_the_oracle_step_by_step(algo):
         committed = [t for s in ref[:k] for t in s["tokens"]]
         if k < min(len(ref), len(got)):
             # first differing step: must be a close call for the oracle
+            print(f"  split at step {k}: oracle margin {ref[k]['margin']:.4f}", flush=True)
             assert ref[k]["margin"] < MARGIN_TOL, (segments, k, ref[k], got[k])
             committed += ref[k]["tokens"]
             splits += 1
