@@ -23,11 +23,14 @@ def _rel_err(got, ref):
     return float((np.abs(got - ref).max(axis=-1) / rng).max())
 
 
-def test_full_width_truncated_pair_matches_oracle():
+@pytest.mark.parametrize("name", ["70b_7b", "33b_1b", "7b_1b", "small"])
+def test_full_width_truncated_pair_matches_oracle(name):
+    """Every workload pair at its real widths (depth cut to 2 target layers and 1 draft layer so that the fp32
+    oracle can hold it): GQA 64/8 and 32/4, MHA with 56 and 16 heads, head_dim 64 and 128, vocab 32000 and 32256."""
     import paper_2408_11850_amd as amd
     from paper_2408_11850_amd import harness
-    cfg = synth.config("70b_7b", depth=2, draft_depth=1)
-    print("full-width truncated pair: generating weights on the GPU", flush=True)
+    cfg = synth.config(name, depth=2, draft_depth=1)
+    print(f"full-width truncated pair {name}: generating weights on the GPU", flush=True)
     tw, dw = synth.make_pair(cfg, device="cuda")            # bf16, the values both sides get
     target, draft = harness.build_pair(cfg, weights=(tw, dw))
     cpu = lambda w: {"tok_embed": w["tok_embed"].cpu(), "lm_head": w["lm_head"].cpu(), "final_norm": w["final_norm"].cpu(),
@@ -53,7 +56,7 @@ def test_full_width_truncated_pair_matches_oracle():
         worst = max(worst, _rel_err(got, ref))
         print(f"  M={m}: logit error / range so far {worst:.2e}", flush=True)
     assert worst <= 2e-2
-    # the draft model (d 4096, MHA): its first sampled token against the oracle's distribution
+    # the draft model: its first sampled token against the oracle's distribution
     od = transformer.CachedModel(dm, 256)
     od.feed(prompt[:-1])
     from oracle import sampling
