@@ -276,6 +276,11 @@ def main():
         for a in (0.5, 0.7, 0.9):
             side[f"pearl_forced_alpha_{a}"] = run(amd.ALGO_PEARL, gamma, a)
             side[f"sd_forced_alpha_{a}"] = run(amd.ALGO_SD, gamma, a)
+        # the two ablations of Section 4.3 on the same kernels (analogue of the paper's ablation table)
+        for a in (None, 0.9):
+            tag = "" if a is None else f"_forced_alpha_{a}"
+            side["pearl_without_pre_verify" + tag] = run(amd.ALGO_PEARL_NO_PRE, gamma, a)
+            side["pearl_without_post_verify" + tag] = run(amd.ALGO_PEARL_NO_POST, gamma, a)
         log(f"[bench] side runs: {json.dumps(side, default=float)}")
 
     traffic = None

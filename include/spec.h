@@ -46,9 +46,12 @@ enum { SPEC_TARGET = 0, SPEC_DRAFT = 1 };
 /* Which acceptance step to run (spec_accept). */
 enum {
   SPEC_ACCEPT_AR = 0,   /* no draft: draw the next token from row 0 of the last target forward      */
-  SPEC_ACCEPT_SD = 1,   /* vanilla speculative decoding, Section 2: rows p_1..p_{g+1} test x_1..x_g */
+  SPEC_ACCEPT_SD = 1,   /* vanilla speculative decoding, Section 2: every row but the last tests a draft,
+                           the last row draws the bonus token when all are accepted                      */
   SPEC_ACCEPT_PRE = 2,  /* pre-verify, Section 3.2 / Algorithm 2: row p = M_p(x) tests x_1          */
-  SPEC_ACCEPT_POST = 3  /* post-verify, Section 3.3 / Algorithm 2: row P_i tests x_{i+1}, i=1..g   */
+  SPEC_ACCEPT_POST = 3  /* post-verify, Section 3.3 / Algorithm 2: every row tests a draft, no bonus.
+                           For SD and POST row 0 tests x_1, or x_2 when x_1 is already committed (it then
+                           was the first token of the verify forward)                                    */
 };
 enum { SPEC_MODE_PRE = 0, SPEC_MODE_POST = 1 };
 
@@ -148,9 +151,12 @@ int spec_kv_free_pages(const spec_ctx* ctx, int which);
 long long spec_forward_count(const spec_ctx* ctx, int which); /* forwards run so far by that model */
 
 /* Whole loops on top of the calls above (host control flow only): Algorithm 1/2 (algo 2), vanilla
- * speculative decoding (algo 1), autoregressive decoding (algo 0).  Uniform arrays are indexed
+ * speculative decoding (algo 1), autoregressive decoding (algo 0), and the two ablations of Section 4.3:
+ * PEARL without pre-verify (algo 3: after a rejection one step only drafts, then the target verifies the frontier
+ * and x_1..x_gamma while the draft goes on) and without post-verify (algo 4: x_1 is verified early, then the target
+ * verifies x_2..x_gamma and draws a bonus token while the draft model idles).  Uniform arrays are indexed
  * by step: u_draft[t*gamma + i], r_accept[t*(gamma+1) + i], u_resample[t]; each must hold
- * n_generate steps.  The loop ends after n_generate tokens, or after max_steps steps if
+ * n_generate steps (2 n_generate for algo 3, whose draft-only steps commit nothing).  The loop ends after n_generate tokens, or after max_steps steps if
  * max_steps > 0.  force_bits == NULL uses real decisions; otherwise decision (t, i) is taken
  * from force_bits[t*(gamma+1)+i] (measurement only).  out_tokens_host receives the committed
  * tokens (at most n_generate; stats[1] tells how many were committed).

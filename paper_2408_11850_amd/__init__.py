@@ -19,6 +19,7 @@ SPEC_MODE_PRE, SPEC_MODE_POST = 0, 1
 SPEC_MAX_TOKENS = 32
 PAGE_TOKENS = 64
 ALGO_AR, ALGO_SD, ALGO_PEARL = 0, 1, 2
+ALGO_PEARL_NO_PRE, ALGO_PEARL_NO_POST = 3, 4      # the two ablations
 SPEC_OPT_GEMM_WGS_PER_CU = 1
 SPEC_OPT_GRAPHS = 2
 

@@ -204,7 +204,8 @@ class SpecContext:
         f32 = lambda a: np.ascontiguousarray(np.asarray(a, dtype=np.float32))
         ud, ra, ur = f32(uniforms.draft), f32(uniforms.accept), f32(uniforms.resample)
         g = max(gamma, 1)
-        need = max_steps if max_steps > 0 else n_generate      # a step commits at least one token
+        # a step commits at least one token, except the draft-only steps of algo 3 (at most every other step)
+        need = max_steps if max_steps > 0 else n_generate * (2 if algo == 3 else 1)
         if algo != ALGO_AR:
             assert ud.shape == (ud.shape[0], g) and ra.shape == (ra.shape[0], g + 1)
             assert ud.shape[0] >= need and ra.shape[0] >= need

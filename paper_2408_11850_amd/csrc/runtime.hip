@@ -520,18 +520,18 @@ extern "C" int spec_accept(spec_ctx* c, int kind, const float* r, int n_r, float
   a.u_resample = u_resample;
   a.force_mask = force_mask;
   a.n_rows = c->last_verify_rows;
-  int first = 1;   // draft index tested by logits row 0
+  // draft index tested by logits row 0: x_2 when x_1 is already committed (it was the first token fed), else x_1
+  const int first = c->first_verified ? 2 : 1;
   switch (kind) {
     case SPEC_ACCEPT_AR: a.n_test = 0; break;
-    case SPEC_ACCEPT_SD: a.n_test = c->last_verify_rows - 1; first = 1; break;
-    case SPEC_ACCEPT_PRE: a.n_test = 1; first = 1; break;
-    case SPEC_ACCEPT_POST: a.n_test = c->last_verify_rows; first = 2; break;
+    case SPEC_ACCEPT_SD: a.n_test = c->last_verify_rows - 1; break;    // the last row draws the bonus token
+    case SPEC_ACCEPT_PRE: a.n_test = 1; break;
+    case SPEC_ACCEPT_POST: a.n_test = c->last_verify_rows; break;      // every row tests a draft, no bonus
     default: FAIL(SPEC_E_INVAL, "unknown accept kind %d", kind);
   }
   if (c->last_verify_rows < 1) FAIL(SPEC_E_STATE, "no target forward to accept against");
   if (kind == SPEC_ACCEPT_PRE && c->last_verify_rows != 1) FAIL(SPEC_E_STATE, "pre-verify needs a one-token target forward");
-  if (kind == SPEC_ACCEPT_POST && !c->first_verified) FAIL(SPEC_E_STATE, "post-verify needs an accepted first draft token");
-  if (kind != SPEC_ACCEPT_POST && kind != SPEC_ACCEPT_AR && c->first_verified) FAIL(SPEC_E_STATE, "pending drafts belong to a post-verify step");
+  if (kind == SPEC_ACCEPT_PRE && c->first_verified) FAIL(SPEC_E_STATE, "pre-verify needs fresh drafts, but x_1 is already committed");
   if (first + a.n_test - 1 > c->n_drafted) FAIL(SPEC_E_STATE, "%d drafts to test, %d drafted", a.n_test, c->n_drafted);
   if (a.n_test > 0 && (!r || n_r < a.n_test)) FAIL(SPEC_E_INVAL, "%d acceptance uniforms needed", a.n_test);
   for (int i = 0; i < a.n_test; ++i) {
@@ -576,8 +576,11 @@ extern "C" int spec_accept(spec_ctx* c, int kind, const float* r, int n_r, float
     case SPEC_ACCEPT_POST:
       for (int i = 0; i < n; ++i) tokens_out[no++] = res.ring[a.slot[i]];
       if (n == a.n_test) {
-        c->ring_base = (c->ring_base + a.n_test) % c->ring_n;
-        c->n_drafted -= a.n_test;
+        // the last accepted draft x_L (L = first + n_test - 1) is the new frontier and becomes x_1
+        const int shift = first + a.n_test - 2;
+        c->ring_base = (c->ring_base + shift) % c->ring_n;
+        c->n_drafted -= shift;
+        c->first_verified = true;
         *next_mode = SPEC_MODE_POST;
       } else {
         tokens_out[no++] = res.token;
@@ -644,7 +647,8 @@ extern "C" int spec_generate(spec_ctx* c, int algo, int gamma, int n_generate, i
                              const float* r_accept, const float* u_resample, const uint8_t* force_bits,
                              int32_t* out_tokens, double* stats) {
   if (!c || !out_tokens || !u_resample) FAIL(SPEC_E_INVAL, "null argument");
-  if (algo < 0 || algo > 2) FAIL(SPEC_E_INVAL, "algo must be 0 (AR), 1 (SD) or 2 (PEARL)");
+  if (algo < 0 || algo > 4)
+    FAIL(SPEC_E_INVAL, "algo must be 0 (AR), 1 (SD), 2 (PEARL), 3 (PEARL w/o pre-verify) or 4 (PEARL w/o post-verify)");
   if (algo > 0 && (gamma < 1 || gamma > c->cfg.gamma_max || !u_draft || !r_accept)) FAIL(SPEC_E_INVAL, "bad gamma / uniforms");
   if (n_generate < 1) FAIL(SPEC_E_INVAL, "n_generate must be positive");
   if (!c->prefilled) FAIL(SPEC_E_STATE, "spec_prefill has not run");
@@ -652,7 +656,7 @@ extern "C" int spec_generate(spec_ctx* c, int algo, int gamma, int n_generate, i
   const int wgs_before = c->wgs;
   // while the two streams overlap, one projection workgroup per CU and stream is better from gamma 6 on (long draft chains),
   // two per CU below that (measured on the 70B/7B-shape pair)
-  if (c->wgs_opt < 0) c->wgs = ((algo == 2) && (c->m[0].stream != c->m[1].stream) && gamma >= 6) ? SPEC_PEARL_WGS_PER_CU : 2;
+  if (c->wgs_opt < 0) c->wgs = ((algo >= 2) && (c->m[0].stream != c->m[1].stream) && gamma >= 6) ? SPEC_PEARL_WGS_PER_CU : 2;
   int mode = c->mode;
   int produced = 0, rc = 0;
   long long steps = 0, accepted = 0, tested = 0, post_steps = 0;
@@ -674,6 +678,28 @@ extern "C" int spec_generate(spec_ctx* c, int algo, int gamma, int n_generate, i
       for (int i = 0; i < gamma; ++i)
         if ((rc = spec_draft_step(c, u_draft[t * gamma + i], nullptr))) return rc;
       if ((rc = spec_verify(c, nullptr, gamma + 1, nullptr))) return rc;
+    } else if (algo == 3) {
+      // PEARL without pre-verify: after a rejection one step only drafts; every other step verifies what is
+      // pending (the first time together with the frontier: gamma + 1 rows) while the draft goes on
+      if (c->n_drafted == 0) {
+        for (int i = 0; i < gamma; ++i)
+          if ((rc = spec_draft_step(c, u_draft[t * gamma + i], nullptr))) return rc;
+        steps++;
+        continue;
+      }
+      kind = SPEC_ACCEPT_POST;
+      n_test = c->first_verified ? gamma : gamma + 1;
+      post_steps++;
+      if ((rc = spec_verify(c, nullptr, n_test, nullptr))) return rc;
+      for (int i = 0; i < gamma; ++i)
+        if ((rc = spec_draft_step(c, u_draft[t * gamma + i], nullptr))) return rc;
+    } else if (algo == 4 && mode == SPEC_MODE_POST) {
+      // PEARL without post-verify: x_1 was accepted early; the target verifies x_2..x_gamma (bonus token from the
+      // last row) while the draft model idles
+      kind = SPEC_ACCEPT_SD;
+      n_test = gamma - 1;
+      post_steps++;
+      if ((rc = spec_verify(c, nullptr, gamma, nullptr))) return rc;
     } else if (mode == SPEC_MODE_PRE) {
       kind = SPEC_ACCEPT_PRE;
       n_test = 1;
