@@ -189,6 +189,16 @@ size_t spec_gemm_workspace_bytes(int M, int N, int K);
 int spec_gemm_partials(const void* x_dev, const void* w_packed_dev, int M, int N, int K,
                        void* work_dev, void* stream);
 
+/* The prompt-sized projection of spec_prefill's dense path (matrix-core bound, any M >= 1):
+ *   epilogue 0: y[M][N] (fp32, device)  = x[M][K] W^T
+ *   epilogue 1: y[M][N] (fp32, device) += x[M][K] W^T                      (residual add)
+ *   epilogue 2: z[M][N/2] (bf16, device) = silu(gate) * up, where W holds the gate and up matrices
+ *               with their 16-row panels interleaved (even panel = gate, odd = up)
+ * x is bf16 row-major, W panel-packed (spec_pack_weight).  N % 16 == 0 and K % 32 == 0 are required
+ * (N % 32 == 0 for epilogue 2); the unused one of y / z may be NULL.  Asynchronous on `stream`. */
+int spec_dense_gemm(float* y_dev, void* z_dev, const void* x_dev, const void* w_packed_dev, int M, int N, int K,
+                    int epilogue, void* stream);
+
 /* Streaming-read probe: sums `bytes` bytes of device memory with 16-byte loads; used to
  * measure the achievable HBM read ceiling next to the nominal peak.  out_dev: 4 bytes. */
 int spec_read_probe(const void* src_dev, size_t bytes, void* out_dev, void* stream);
@@ -212,8 +222,13 @@ int spec_accept_rows(const float* p_logits_dev, int n_rows, const float* q_rows_
  * PEARL loop on two different streams uses 1, everything else 2.  Results do not depend on it (the K split
  * and the order of additions are fixed by the shape).
  * SPEC_OPT_GRAPHS: 1 (default) = every forward is captured once per (model, token count, mode) into a HIP graph
- * and replayed; 0 = launch kernel by kernel.  Results are identical. */
-enum { SPEC_OPT_GEMM_WGS_PER_CU = 1, SPEC_OPT_GRAPHS = 2 };
+ * and replayed; 0 = launch kernel by kernel.  Results are identical.
+ * SPEC_OPT_PREFILL: how spec_prefill feeds the prompt.  1 = dense path: blocks of up to 4096 tokens go through
+ * matrix-core GEMMs and a causal flash-attention kernel (needs d_model, n_heads*head_dim and d_ffn to be
+ * multiples of 32, else SPEC_E_INVAL at spec_prefill); 0 = as a sequence of 32-token verify forwards (the
+ * decode kernels); -1 (default) = dense when the shapes allow it and the prompt has more than 64 tokens.
+ * Both fill the caches with the same K / V up to bf16 rounding of differently ordered sums. */
+enum { SPEC_OPT_GEMM_WGS_PER_CU = 1, SPEC_OPT_GRAPHS = 2, SPEC_OPT_PREFILL = 3 };
 int spec_set_option(spec_ctx* ctx, int option, int value);
 
 /* Run-time switches: bit 0 = record HIP events around every projection launch of the

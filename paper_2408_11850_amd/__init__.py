@@ -22,6 +22,8 @@ ALGO_AR, ALGO_SD, ALGO_PEARL = 0, 1, 2
 ALGO_PEARL_NO_PRE, ALGO_PEARL_NO_POST = 3, 4      # the two ablations
 SPEC_OPT_GEMM_WGS_PER_CU = 1
 SPEC_OPT_GRAPHS = 2
+SPEC_OPT_PREFILL = 3
+EPI_STORE, EPI_RESID, EPI_SWIGLU = 0, 1, 2
 
 
 class ModelDesc(C.Structure):
@@ -71,6 +73,7 @@ SIGNATURES = {
     "spec_gemm": (C.c_int, [_P, _P, _P, C.c_int, C.c_int, C.c_int, _P, _P]),
     "spec_gemm_workspace_bytes": (C.c_size_t, [C.c_int, C.c_int, C.c_int]),
     "spec_gemm_partials": (C.c_int, [_P, _P, C.c_int, C.c_int, C.c_int, _P, _P]),
+    "spec_dense_gemm": (C.c_int, [_P, _P, _P, _P, C.c_int, C.c_int, C.c_int, C.c_int, _P]),
     "spec_read_probe": (C.c_int, [_P, C.c_size_t, _P, _P]),
     "spec_sample_row": (C.c_int, [_P, C.c_int, C.c_float, C.c_float, C.c_float, _P, _P, _P]),
     "spec_accept_rows": (C.c_int, [_P, C.c_int, _P, _P, C.c_int, C.c_int, C.c_float, C.c_float, _PF, C.c_float,
@@ -111,4 +114,4 @@ def check(rc: int) -> int:
     return rc
 
 
-from .binding import SpecContext, pack_model, gemm, sample_row, accept_rows, read_probe  # noqa: E402,F401
+from .binding import SpecContext, pack_model, gemm, dense_gemm, sample_row, accept_rows, read_probe  # noqa: E402,F401

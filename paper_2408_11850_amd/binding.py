@@ -258,6 +258,28 @@ def gemm(x: torch.Tensor, w_packed: torch.Tensor, N: int, partials_only: bool = 
     return y
 
 
+def dense_gemm(x: torch.Tensor, w_packed: torch.Tensor, N: int, epilogue: int = 0,
+               y: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """The prompt-sized matrix-core projection, on torch's current stream.
+
+    epilogue 0: returns y[M][N] fp32 = x W^T; 1: adds x W^T into the given y; 2: returns z[M][N/2] bf16 =
+    silu(gate) * up for a gate/up matrix with interleaved 16-row panels."""
+    lib = load_library()
+    assert x.dtype == torch.bfloat16 and x.is_contiguous() and x.is_cuda
+    M, K = x.shape
+    st = _stream_ptr(torch.cuda.current_stream())
+    if epilogue == 2:
+        z = torch.empty((M, N // 2), dtype=torch.bfloat16, device=x.device)
+        check(lib.spec_dense_gemm(None, _ptr(z), _ptr(x), _ptr(w_packed), M, N, K, 2, st))
+        return z
+    if epilogue == 1:
+        assert y is not None and y.dtype == torch.float32 and y.is_contiguous() and tuple(y.shape) == (M, N)
+    else:
+        y = torch.empty((M, N), dtype=torch.float32, device=x.device)
+    check(lib.spec_dense_gemm(_ptr(y), None, _ptr(x), _ptr(w_packed), M, N, K, epilogue, st))
+    return y
+
+
 def sample_row(logits: torch.Tensor, temperature: float, logit_scale: float, u: float):
     lib = load_library()
     assert logits.dtype == torch.float32 and logits.is_contiguous() and logits.dim() == 1

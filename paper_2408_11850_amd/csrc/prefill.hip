@@ -1,0 +1,357 @@
+// Prompt (prefill) kernels for gfx950: the only compute-bound part of the decoding workload.
+//
+// A prompt of C tokens goes through every projection as one dense GEMM Y[C][N] = X[C][K] W^T, so the
+// contraction has C flop per weight byte pair and belongs on the matrix cores at full tile size,
+// unlike the decode-time projections (<= 32 rows, HBM-bound).  W stays in the panel-packed order the decode
+// kernels stream (16 output rows x 32 k per 1 KiB block = one A operand of v_mfma_f32_16x16x32_bf16);
+// X is row-major bf16, and a 16-token x 32-k block of it gathered with one 16-byte load per lane is exactly
+// one B operand.  Both operand kinds are therefore moved global -> LDS with the LDS-direct loads of gfx950
+// (global_load_lds_dwordx4: lane l lands at base + 16 l, i.e. already in operand order) and read back with
+// one conflict-free ds_read_b128 per fragment.
+//
+// Tiling: workgroup = 8 waves = 256 tokens x 256 outputs, wave = 128 tokens x 64 outputs (8 x 4 MFMA tiles,
+// 128 accumulator registers, two waves per SIMD), K advances 32 per stage through a ring of DG_STAGES LDS
+// buffers of 32 KiB.
+#include "spec_internal.h"
+
+#define DG_BM 256
+#define DG_BN 256
+#define DG_THREADS 512
+#define DG_STAGES 4
+#define DG_STAGE_U4 (32 * 64)          // 16-byte units per stage: 16 weight blocks + 16 activation blocks
+
+enum { DG_EPI_STORE = 0, DG_EPI_RESID = 1, DG_EPI_SWIGLU = 2 };
+
+__device__ __forceinline__ void dg_issue_stage(const u32x4* __restrict__ wsrc[2], const bf16* __restrict__ xsrc[2],
+                                               u32x4* lds_stage, int w, int step) {
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+    __builtin_amdgcn_global_load_lds(wsrc[i] + (size_t)step * 64, lds_stage + (w * 2 + i) * 64, 16, 0, 0);
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+    __builtin_amdgcn_global_load_lds(xsrc[i] + (size_t)step * 32, lds_stage + (16 + w * 2 + i) * 64, 16, 0, 0);
+}
+
+// EPI: STORE  Y[m][n] = acc (fp32);  RESID  Y[m][n] += acc;  SWIGLU  Z[m][f] = silu(gate) * up (bf16) with the
+// gate / up panels interleaved (even panel = gate rows of f-tile j, odd = the matching up rows), N = 2F.
+template <int EPI>
+__global__ __launch_bounds__(DG_THREADS, 2) void dense_gemm_kernel(const bf16* __restrict__ X,
+                                                                   const u32x4* __restrict__ Wp,
+                                                                   float* __restrict__ Y, bf16* __restrict__ Z, int M,
+                                                                   int N, int K, int NT, int steps, int TM, int cx) {
+  extern __shared__ u32x4 lds[];
+  const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
+  // Workgroups are dealt to the 8 XCDs round-robin; XCD x owns tile columns [x cx, (x+1) cx) and walks them in
+  // groups of 4 columns x all row tiles, so the 32 workgroups an XCD runs together share 8 x 4 operand strips
+  // in its L2.
+  const int x = blockIdx.x & 7, j = blockIdx.x >> 3;
+  const int TN = (NT + 15) >> 4;
+  int nx = TN - x * cx;
+  if (nx > cx) nx = cx;
+  const int grp = j / (TM * 4), idx = j % (TM * 4);
+  int gw = nx - grp * 4;          // columns in this group; its tiles are numbered row-major over them
+  if (gw > 4) gw = 4;
+  if (gw <= 0 || idx >= TM * gw) return;
+  const int tm = idx / gw, tn = x * cx + grp * 4 + idx % gw;
+
+  const int c = lane & 15, kb = lane >> 4;
+  const u32x4* wsrc[2];
+  const bf16* xsrc[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    int panel = tn * 16 + w * 2 + i;
+    if (panel > NT - 1) panel = NT - 1;          // clamped rows are computed and never stored
+    wsrc[i] = Wp + (size_t)panel * steps * 64 + lane;
+    int m = tm * DG_BM + (w * 2 + i) * 16 + c;
+    if (m > M - 1) m = M - 1;
+    xsrc[i] = X + (size_t)m * K + kb * 8;
+  }
+
+  f32x4 acc[4][8];
+#pragma unroll
+  for (int a = 0; a < 4; ++a)
+#pragma unroll
+    for (int b = 0; b < 8; ++b) acc[a][b] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  // Pipeline: the LDS-direct loads of step ks + DG_STAGES - 1 are issued while step ks is multiplied.  Steps past
+  // the end reload the last step into a free buffer, which keeps the count of outstanding loads uniform.  The
+  // barrier is a bare s_barrier behind an explicit vmcnt wait: the fence of __syncthreads would drain every
+  // load in flight.
+#pragma unroll
+  for (int s = 0; s < DG_STAGES - 1; ++s)
+    dg_issue_stage(wsrc, xsrc, lds + s * DG_STAGE_U4, w, s < steps ? s : steps - 1);
+  const int wn = w & 3, wm = w >> 2;
+  const u32x4* fa = lds + (wn * 4) * 64 + lane;
+  const u32x4* fb = lds + (16 + wm * 8) * 64 + lane;
+  for (int ks = 0; ks < steps; ++ks) {
+    // this wave's 4 loads of stage ks have landed (8 younger ones may be in flight) ...
+    asm volatile("s_waitcnt vmcnt(8)\n\ts_barrier" ::: "memory");
+    // ... and so have everybody else's; all waves are also done reading stage ks - 1, whose buffer is refilled
+    const int nxt = ks + DG_STAGES - 1;
+    dg_issue_stage(wsrc, xsrc, lds + (nxt % DG_STAGES) * DG_STAGE_U4, w, nxt < steps ? nxt : steps - 1);
+    const int so = (ks % DG_STAGES) * DG_STAGE_U4;
+    bf16x8 a[4], b[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) b[i] = __builtin_bit_cast(bf16x8, fb[so + i * 64]);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) a[i] = __builtin_bit_cast(bf16x8, fa[so + i * 64]);
+#pragma unroll
+    for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+      for (int mt = 0; mt < 8; ++mt)
+        acc[nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[nt], b[mt], acc[nt][mt], 0, 0, 0);
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the redundant tail loads must not outlive the workgroup's LDS
+
+  // acc[nt][mt][r] = Y[m0 + 16 mt + c][n0 + 16 nt + 4 kb + r]
+  const int m0 = tm * DG_BM + wm * 128, n0 = tn * DG_BN + wn * 64;
+#pragma unroll
+  for (int mt = 0; mt < 8; ++mt) {
+    const int m = m0 + mt * 16 + c;
+    if (m >= M) continue;
+    if (EPI == DG_EPI_SWIGLU) {
+      const int F = N >> 1;
+#pragma unroll
+      for (int nt = 0; nt < 4; nt += 2) {
+        const int n = n0 + nt * 16;
+        if (n + 32 > N) continue;
+        const int f = (n >> 1) + kb * 4;
+        const f32x4 g = acc[nt][mt], u = acc[nt + 1][mt];
+        bf16 out[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) out[q] = __float2bfloat16(g[q] / (1.0f + __expf(-g[q])) * u[q]);
+        *reinterpret_cast<uint2*>(Z + (size_t)m * F + f) = *reinterpret_cast<const uint2*>(out);
+      }
+    } else {
+#pragma unroll
+      for (int nt = 0; nt < 4; ++nt) {
+        const int n = n0 + nt * 16 + kb * 4;
+        if (n >= N) continue;
+        f32x4* dst = reinterpret_cast<f32x4*>(Y + (size_t)m * N + n);
+        if (EPI == DG_EPI_RESID) *dst = *dst + acc[nt][mt];
+        else *dst = acc[nt][mt];
+      }
+    }
+  }
+}
+
+size_t dense_gemm_lds_bytes() { return (size_t)DG_STAGES * DG_STAGE_U4 * 16; }
+
+hipError_t launch_dense_gemm(const bf16* x, const void* wp, int M, int N, int K, int epi, float* y, bf16* z,
+                             hipStream_t st) {
+  static bool attr_set = false;
+  const size_t lds_bytes = dense_gemm_lds_bytes();
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void*)dense_gemm_kernel<DG_EPI_STORE>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute((const void*)dense_gemm_kernel<DG_EPI_RESID>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                              (int)lds_bytes);
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute((const void*)dense_gemm_kernel<DG_EPI_SWIGLU>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                              (int)lds_bytes);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  const int NT = N / 16, steps = K / 32;
+  const int TM = (M + DG_BM - 1) / DG_BM, TN = (NT + 15) / 16;
+  const int cx = (TN + 7) / 8;
+  const int groups = (cx + 3) / 4;
+  dim3 grid(8 * groups * TM * 4), block(DG_THREADS);
+  if (epi == DG_EPI_STORE)
+    dense_gemm_kernel<DG_EPI_STORE><<<grid, block, lds_bytes, st>>>(x, (const u32x4*)wp, y, z, M, N, K, NT, steps, TM, cx);
+  else if (epi == DG_EPI_RESID)
+    dense_gemm_kernel<DG_EPI_RESID><<<grid, block, lds_bytes, st>>>(x, (const u32x4*)wp, y, z, M, N, K, NT, steps, TM, cx);
+  else
+    dense_gemm_kernel<DG_EPI_SWIGLU><<<grid, block, lds_bytes, st>>>(x, (const u32x4*)wp, y, z, M, N, K, NT, steps, TM, cx);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// Causal attention of a block of M prompt tokens over the paged KV cache (positions 0 .. len + M - 1, the
+// block's own K / V already appended).  Rows are the M*G (token, query head) pairs of one KV head, token-major,
+// as in the decode kernel; a workgroup of 4 waves owns 256 consecutive rows, a wave 4 tiles of 16.  K and V
+// pages are in MFMA operand order, so every 32-position chunk is 16 KiB (head_dim 128) that the workgroup
+// brings into LDS once with LDS-direct loads and each wave reads as ready-made fragments: S^T = K Q^T,
+// online softmax per query row, O^T += V^T P^T.  Chunks beyond the last position a workgroup's rows may see
+// are never touched (causal skip), and the workgroups with the longest ranges are scheduled first.
+// ---------------------------------------------------------------------------------------------------------
+#define PA_WAVES 4
+#define PA_QT 4                                  // 16-row tiles per wave
+#define PA_ROWS (PA_WAVES * PA_QT * 16)          // rows per workgroup
+#define PA_STAGES 3
+#define PA_NEG_BIG (-1.0e30f)
+
+// Brings chunk `ch` (32 positions) of one KV head into an LDS stage.  Block b of a chunk: b < KB -> K block b
+// (lane-linear in the page), else V block b - KB, whose lane (c, g4) sits at byte c*64 + g4*16 of the block.
+template <int DH>
+__device__ __forceinline__ void pa_issue(const bf16* __restrict__ pool, const int* __restrict__ block_table,
+                                         const KvGeom& g, int layer, int kvh, int ch, u32x4* lds_stage, int w,
+                                         int lane) {
+  constexpr int KB = 2 * (DH / 32), VB = DH / 16, LPW = (KB + VB) / PA_WAVES;
+  const int c = lane & 15, g4 = lane >> 4;
+  const int pos0 = ch << 5;
+  const int page = block_table[pos0 / SPEC_PAGE_TOKENS];
+  const int inpage = pos0 % SPEC_PAGE_TOKENS;
+  const u32x4* kblk = reinterpret_cast<const u32x4*>(pool + g.offset(page, layer, 0, kvh)) +
+                      (size_t)(inpage >> 4) * (DH / 32) * 64 + lane;
+  const bf16* vblk = pool + g.offset(page, layer, 1, kvh) + (size_t)(inpage >> 5) * DH * 32;
+#pragma unroll
+  for (int i = 0; i < LPW; ++i) {
+    const int b = w * LPW + i;
+    const void* src = (b < KB) ? (const void*)(kblk + (size_t)b * 64)
+                               : (const void*)(vblk + ((size_t)((b - KB) * 16 + c) * 32 + g4 * 8));
+    __builtin_amdgcn_global_load_lds(src, lds_stage + b * 64, 16, 0, 0);
+  }
+}
+
+template <int DH>
+__global__ __launch_bounds__(PA_WAVES * 64, 1) void prefill_attn_kernel(const bf16* __restrict__ q,
+                                                                        const bf16* __restrict__ pool,
+                                                                        const int* __restrict__ block_table,
+                                                                        const int* __restrict__ len_ptr, KvGeom g,
+                                                                        int layer, int M, int Hq, float scale,
+                                                                        bf16* __restrict__ out) {
+  constexpr int KB = 2 * (DH / 32);              // K blocks (1 KiB) per chunk
+  constexpr int VB = DH / 16;                    // V blocks per chunk
+  constexpr int NB = KB + VB;
+  constexpr int LPW = NB / PA_WAVES;             // LDS-direct loads per wave and chunk
+  __shared__ u32x4 lds[PA_STAGES][NB][64];
+  const int kvh = blockIdx.y;
+  const int rb = gridDim.x - 1 - blockIdx.x;     // longest ranges first
+  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int c = lane & 15, g4 = lane >> 4;
+  const int Hkv = g.n_kv_heads, G = Hq / Hkv, R = M * G;
+  const int len = len_ptr[0];
+  const int r0 = rb * PA_ROWS;
+  int rlast = r0 + PA_ROWS - 1;
+  if (rlast > R - 1) rlast = R - 1;
+  const int nch = ((len + rlast / G) >> 5) + 1;  // chunks this workgroup needs
+  int wlast = r0 + (w + 1) * PA_QT * 16 - 1;
+  if (wlast > R - 1) wlast = R - 1;
+  const int wave_limit = (r0 + w * PA_QT * 16 < R) ? len + wlast / G : -1;
+
+  // per q tile: row of this lane, its visibility limit and its Q fragments
+  int limit[PA_QT];
+  bf16x8 qf[PA_QT][DH / 32];
+#pragma unroll
+  for (int t = 0; t < PA_QT; ++t) {
+    const int Rr = r0 + (w * PA_QT + t) * 16 + c;
+    const bool valid = Rr < R;
+    const int tok = valid ? Rr / G : 0;
+    const int head = kvh * G + (valid ? Rr % G : 0);
+    limit[t] = valid ? len + tok : -1;
+#pragma unroll
+    for (int j = 0; j < DH / 32; ++j) {
+      u32x4 v = {0u, 0u, 0u, 0u};
+      if (valid) v = *reinterpret_cast<const u32x4*>(q + ((size_t)tok * Hq + head) * DH + j * 32 + g4 * 8);
+      qf[t][j] = __builtin_bit_cast(bf16x8, v);
+    }
+  }
+
+  float m_run[PA_QT], l_run[PA_QT];
+  f32x4 o[PA_QT][DH / 16];
+#pragma unroll
+  for (int t = 0; t < PA_QT; ++t) {
+    m_run[t] = PA_NEG_BIG;
+    l_run[t] = 0.f;
+#pragma unroll
+    for (int dt = 0; dt < DH / 16; ++dt) o[t][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+
+  pa_issue<DH>(pool, block_table, g, layer, kvh, 0, &lds[0][0][0], w, lane);
+  pa_issue<DH>(pool, block_table, g, layer, kvh, nch > 1 ? 1 : 0, &lds[1][0][0], w, lane);
+  for (int ch = 0; ch < nch; ++ch) {
+    // stage ch has landed for this wave (one younger stage may be in flight), then for everybody
+    if (LPW == 4) asm volatile("s_waitcnt vmcnt(4)\n\ts_barrier" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(2)\n\ts_barrier" ::: "memory");
+    pa_issue<DH>(pool, block_table, g, layer, kvh, ch + 2 < nch ? ch + 2 : nch - 1, &lds[(ch + 2) % PA_STAGES][0][0], w,
+                 lane);
+    const int pos0 = ch << 5;
+    if (pos0 > wave_limit) continue;           // nothing visible for this wave's rows (uniform per wave)
+    const int stg = ch % PA_STAGES;
+    bf16x8 kf[2][DH / 32], vf[DH / 16];
+#pragma unroll
+    for (int t2 = 0; t2 < 2; ++t2)
+#pragma unroll
+      for (int j = 0; j < DH / 32; ++j) kf[t2][j] = __builtin_bit_cast(bf16x8, lds[stg][t2 * (DH / 32) + j][lane]);
+#pragma unroll
+    for (int dt = 0; dt < DH / 16; ++dt) vf[dt] = __builtin_bit_cast(bf16x8, lds[stg][KB + dt][lane]);
+
+#pragma unroll
+    for (int t = 0; t < PA_QT; ++t) {
+      f32x4 s[2];
+#pragma unroll
+      for (int t2 = 0; t2 < 2; ++t2) {
+        s[t2] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int j = 0; j < DH / 32; ++j)
+          s[t2] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[t2][j], qf[t][j], s[t2], 0, 0, 0);
+      }
+      // s[t2][r] = score of position pos0 + 16 t2 + 4 g4 + r for query row c of tile t
+      float mx = PA_NEG_BIG;
+#pragma unroll
+      for (int t2 = 0; t2 < 2; ++t2)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int pos = pos0 + t2 * 16 + g4 * 4 + r;
+          const float v = (pos <= limit[t]) ? s[t2][r] * scale : PA_NEG_BIG;
+          s[t2][r] = v;
+          mx = fmaxf(mx, v);
+        }
+      mx = fmaxf(mx, __shfl_xor(mx, 16));
+      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      const float m_new = fmaxf(m_run[t], mx);
+      const float corr = __expf(m_run[t] - m_new);
+      float psum = 0.f;
+      bf16x8 pf;
+#pragma unroll
+      for (int t2 = 0; t2 < 2; ++t2)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const float p = (s[t2][r] > 0.5f * PA_NEG_BIG) ? __expf(s[t2][r] - m_new) : 0.f;
+          psum += p;
+          pf[t2 * 4 + r] = (__bf16)p;
+        }
+      l_run[t] = l_run[t] * corr + psum;
+      m_run[t] = m_new;
+#pragma unroll
+      for (int dt = 0; dt < DH / 16; ++dt) {
+        o[t][dt] *= corr;
+        o[t][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[dt], pf, o[t][dt], 0, 0, 0);
+      }
+    }
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the redundant tail loads must not outlive the workgroup's LDS
+
+#pragma unroll
+  for (int t = 0; t < PA_QT; ++t) {
+    float l = l_run[t];
+    l += __shfl_xor(l, 16);
+    l += __shfl_xor(l, 32);
+    const int Rr = r0 + (w * PA_QT + t) * 16 + c;
+    if (Rr >= R) continue;
+    const int tok = Rr / G, head = kvh * G + Rr % G;
+    const float inv = 1.0f / l;
+    bf16* dst = out + ((size_t)tok * Hq + head) * DH + g4 * 4;
+#pragma unroll
+    for (int dt = 0; dt < DH / 16; ++dt) {
+      bf16 v4[4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) v4[r] = __float2bfloat16(o[t][dt][r] * inv);
+      *reinterpret_cast<uint2*>(dst + dt * 16) = *reinterpret_cast<const uint2*>(v4);
+    }
+  }
+}
+
+hipError_t launch_prefill_attention(const bf16* q, const bf16* pool, const int* block_table, const int* len_ptr,
+                                    KvGeom g, int layer, int M, int Hq, bf16* out, hipStream_t st) {
+  const int Hkv = g.n_kv_heads, G = Hq / Hkv, R = M * G, dh = g.head_dim;
+  dim3 grid((R + PA_ROWS - 1) / PA_ROWS, Hkv), block(PA_WAVES * 64);
+  const float scale = 1.0f / sqrtf((float)dh);
+  if (dh == 128)
+    prefill_attn_kernel<128><<<grid, block, 0, st>>>(q, pool, block_table, len_ptr, g, layer, M, Hq, scale, out);
+  else
+    prefill_attn_kernel<64><<<grid, block, 0, st>>>(q, pool, block_table, len_ptr, g, layer, M, Hq, scale, out);
+  return hipGetLastError();
+}

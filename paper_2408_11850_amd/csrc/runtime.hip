@@ -56,6 +56,11 @@ struct ModelRt {
   int split_tokens = 0;           // context length the attention split count is sized for (fixed per context)
   // captured forwards, keyed [tokens][logit mode 0/1/2][projection workgroups per CU]
   hipGraphExec_t graphs[SPEC_MAX_TOKENS + 1][3][3] = {};
+  // activation buffers of the dense prompt path, allocated at its first use for pf_cap tokens
+  int pf_cap = 0;
+  int* pf_tok = nullptr;
+  float *pf_h = nullptr, *pf_y = nullptr;
+  bf16 *pf_a = nullptr, *pf_q = nullptr, *pf_attn = nullptr, *pf_z = nullptr;
 };
 
 struct ProfEvents {
@@ -88,6 +93,7 @@ struct spec_ctx {
   bool use_graphs = true;         // replay captured forwards instead of launching ~10 kernels per layer
   int wgs_opt = -1;               // projection workgroups per CU: -1 = automatic, 1, 2
   int wgs = 2;                    // what the next forward uses
+  int prefill_opt = -1;           // -1 automatic, 0 = 32-token verify forwards, 1 = dense path
   ProfEvents prof;
 };
 
@@ -178,7 +184,7 @@ void free_model(ModelRt& m) {
           g = nullptr;
         }
   void* ptrs[] = {m.pool, m.block_table_dev, m.len_dev, m.tok_in, m.h, m.a, m.qbuf, m.attn_out, m.z, m.partials,
-                  m.opart, m.logits};
+                  m.opart, m.logits, m.pf_tok, m.pf_h, m.pf_y, m.pf_a, m.pf_q, m.pf_attn, m.pf_z};
   for (void* p : ptrs)
     if (p) (void)hipFree(p);
 }
@@ -317,6 +323,60 @@ int forward(spec_ctx* c, int which, const TokenSrc& src, int logit_rows) {
   return SPEC_OK;
 }
 
+bool dense_shapes_ok(const spec_model_desc& d) {
+  return d.d_model % 32 == 0 && (d.n_heads * d.head_dim) % 32 == 0 && d.d_ffn % 32 == 0;
+}
+
+int ensure_prefill_buffers(ModelRt& m) {
+  if (m.pf_cap) return SPEC_OK;
+  const spec_model_desc& d = m.d;
+  int cap = m.n_pages * SPEC_PAGE_TOKENS;
+  if (cap > SPEC_PREFILL_BLOCK_MAX) cap = SPEC_PREFILL_BLOCK_MAX;
+  const size_t C = (size_t)cap;
+  const int HD = d.n_heads * d.head_dim, qkvN = (d.n_heads + 2 * d.n_kv_heads) * d.head_dim;
+  const int amax = d.d_model > HD ? d.d_model : HD;
+  int rc;
+  if ((rc = dev_alloc(&m.pf_tok, C))) return rc;
+  if ((rc = dev_alloc(&m.pf_h, C * d.d_model))) return rc;
+  if ((rc = dev_alloc(&m.pf_y, C * qkvN))) return rc;
+  if ((rc = dev_alloc(&m.pf_a, C * amax))) return rc;
+  if ((rc = dev_alloc(&m.pf_q, C * HD))) return rc;
+  if ((rc = dev_alloc(&m.pf_attn, C * HD))) return rc;
+  if ((rc = dev_alloc(&m.pf_z, C * d.d_ffn))) return rc;
+  m.pf_cap = cap;
+  return SPEC_OK;
+}
+
+// One dense pass of model `which` over C prompt tokens (host ids `tok`) at positions len .. len + C - 1:
+// the same chain of operations as enqueue_forward without the LM head, every projection one matrix-core GEMM.
+int prefill_dense_block(spec_ctx* c, int which, const int32_t* tok, int C) {
+  ModelRt& m = c->m[which];
+  const spec_model_desc& d = m.d;
+  hipStream_t st = m.stream;
+  int rc;
+  if ((rc = ensure_pages(m, m.len + C))) return rc;
+  HIPCHK(hipMemcpyAsync(m.pf_tok, tok, (size_t)C * sizeof(int), hipMemcpyHostToDevice, st));
+  HIPCHK(launch_embed(m.pf_h, (const bf16*)m.tok_embed, m.pf_tok, C, d.d_model, d.vocab, st));
+  const int qkvN = (d.n_heads + 2 * d.n_kv_heads) * d.head_dim;
+  const int HD = d.n_heads * d.head_dim;
+  for (int l = 0; l < d.n_layers; ++l) {
+    HIPCHK(launch_addnorm(m.pf_h, nullptr, 0, (const bf16*)m.attn_norm[l], m.pf_a, C, d.d_model, d.rms_eps, st));
+    HIPCHK(launch_dense_gemm(m.pf_a, m.wqkv[l], C, qkvN, d.d_model, 0, m.pf_y, nullptr, st));
+    HIPCHK(launch_rope_append(m.pf_y, 1, m.pf_q, m.pool, m.block_table_dev, m.len_dev, m.geom, l, C, d.n_heads,
+                              d.rope_theta, st));
+    HIPCHK(launch_prefill_attention(m.pf_q, m.pool, m.block_table_dev, m.len_dev, m.geom, l, C, d.n_heads, m.pf_attn,
+                                    st));
+    HIPCHK(launch_dense_gemm(m.pf_attn, m.wo[l], C, d.d_model, HD, 1, m.pf_h, nullptr, st));
+    HIPCHK(launch_addnorm(m.pf_h, nullptr, 0, (const bf16*)m.ffn_norm[l], m.pf_a, C, d.d_model, d.rms_eps, st));
+    HIPCHK(launch_dense_gemm(m.pf_a, m.wgu[l], C, 2 * d.d_ffn, d.d_model, 2, nullptr, m.pf_z, st));
+    HIPCHK(launch_dense_gemm(m.pf_z, m.wdown[l], C, d.d_model, d.d_ffn, 1, m.pf_h, nullptr, st));
+  }
+  HIPCHK(launch_add_int(m.len_dev, C, st));
+  m.len += C;
+  m.n_forwards++;
+  return SPEC_OK;
+}
+
 void reset_ring(spec_ctx* c) {
   c->ring_base = 0;
   c->n_drafted = 0;
@@ -407,6 +467,9 @@ extern "C" int spec_prefill(spec_ctx* c, const int32_t* prompt, int n_prompt, in
   for (int w = 0; w < 2; ++w)
     if (n_prompt - 1 + 2 * c->cfg.gamma_max > c->m[w].n_pages * SPEC_PAGE_TOKENS)
       FAIL(SPEC_E_NOMEM, "prompt of %d tokens does not fit max_seq", n_prompt);
+  for (int w = 0; w < 2; ++w)
+    if (((which_mask >> w) & 1) && c->prefill_opt == 1 && !dense_shapes_ok(c->m[w].d))
+      FAIL(SPEC_E_INVAL, "dense prefill needs d_model, n_heads*head_dim and d_ffn to be multiples of 32");
   int rc;
   HIPCHK(hipStreamSynchronize(c->m[0].stream));
   HIPCHK(hipStreamSynchronize(c->m[1].stream));
@@ -419,6 +482,15 @@ extern "C" int spec_prefill(spec_ctx* c, const int32_t* prompt, int n_prompt, in
   c->mode = SPEC_MODE_PRE;
   for (int w = 0; w < 2; ++w) {
     if (!((which_mask >> w) & 1)) continue;
+    if (c->prefill_opt == 1 || (c->prefill_opt < 0 && dense_shapes_ok(c->m[w].d) && n_prompt - 1 > 64)) {
+      if ((rc = ensure_prefill_buffers(c->m[w]))) return rc;
+      // the ids are copied from the context's own copy of the prompt, which outlives the asynchronous copy
+      for (int s = 0; s < n_prompt - 1; s += c->m[w].pf_cap) {
+        const int n = (n_prompt - 1 - s) < c->m[w].pf_cap ? (n_prompt - 1 - s) : c->m[w].pf_cap;
+        if ((rc = prefill_dense_block(c, w, c->committed.data() + s, n))) return rc;
+      }
+      continue;
+    }
     for (int s = 0; s < n_prompt - 1; s += SPEC_MAX_TOKENS) {
       TokenSrc src;
       src.n = (n_prompt - 1 - s) < SPEC_MAX_TOKENS ? (n_prompt - 1 - s) : SPEC_MAX_TOKENS;
@@ -790,6 +862,16 @@ extern "C" int spec_gemm(float* y, const void* x, const void* w, int M, int N, i
   return SPEC_OK;
 }
 
+extern "C" int spec_dense_gemm(float* y, void* z, const void* x, const void* w, int M, int N, int K, int epilogue,
+                               void* stream) {
+  if (!x || !w) FAIL(SPEC_E_INVAL, "null pointer");
+  if (epilogue < 0 || epilogue > 2) FAIL(SPEC_E_INVAL, "epilogue must be 0, 1 or 2");
+  if (M < 1 || N < 16 || N % 16 || K < 32 || K % 32) FAIL(SPEC_E_INVAL, "need M >= 1, N %% 16 == 0, K %% 32 == 0");
+  if (epilogue == 2 ? (!z || N % 32) : !y) FAIL(SPEC_E_INVAL, "output pointer missing (or N %% 32 != 0 for epilogue 2)");
+  HIPCHK(launch_dense_gemm((const bf16*)x, w, M, N, K, epilogue, y, (bf16*)z, (hipStream_t)stream));
+  return SPEC_OK;
+}
+
 extern "C" int spec_read_probe(const void* src, size_t bytes, void* out, void* stream) {
   if (!src || !out || bytes < 16) FAIL(SPEC_E_INVAL, "bad argument");
   HIPCHK(launch_read_probe(src, bytes, out, (hipStream_t)stream));
@@ -852,6 +934,11 @@ extern "C" int spec_set_option(spec_ctx* c, int option, int value) {
   if (option == SPEC_OPT_GRAPHS) {
     if (value != 0 && value != 1) FAIL(SPEC_E_INVAL, "SPEC_OPT_GRAPHS takes 0 or 1");
     c->use_graphs = value == 1;
+    return SPEC_OK;
+  }
+  if (option == SPEC_OPT_PREFILL) {
+    if (value < -1 || value > 1) FAIL(SPEC_E_INVAL, "SPEC_OPT_PREFILL takes -1, 0 or 1");
+    c->prefill_opt = value;
     return SPEC_OK;
   }
   FAIL(SPEC_E_INVAL, "unknown option %d", option);

@@ -82,6 +82,13 @@ hipError_t launch_attention(const bf16* q, const bf16* pool, const int* block_ta
 size_t attention_workspace_floats(int Hq, int Hkv, int dh, int max_seq);
 hipError_t launch_silu_mul(const float* partials, int S, bf16* z, int M, int F, hipStream_t st);
 
+// prompt-sized (matrix-core bound) kernels: epilogue 0 = store fp32, 1 = add into fp32, 2 = silu(gate)*up -> bf16
+#define SPEC_PREFILL_BLOCK_MAX 4096   // most prompt tokens one dense pass takes
+hipError_t launch_dense_gemm(const bf16* x, const void* wp, int M, int N, int K, int epi, float* y, bf16* z,
+                             hipStream_t st);
+hipError_t launch_prefill_attention(const bf16* q, const bf16* pool, const int* block_table, const int* len_ptr,
+                                    KvGeom g, int layer, int M, int Hq, bf16* out, hipStream_t st);
+
 // sampling / acceptance
 struct AcceptArgs {
   int kind;                 // SPEC_ACCEPT_*
