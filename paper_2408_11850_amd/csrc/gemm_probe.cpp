@@ -4,6 +4,10 @@
 // Weights are a constant byte pattern (traffic and timing do not depend on the values).
 //
 //   gemm_probe [M=7] [iters=5] [d_model=8192] [n_heads=64] [n_kv_heads=8] [d_ffn=28672] [vocab=32000]
+//   gemm_probe dense [M=4095] [iters=5] [d_model=8192] [n_heads=64] [n_kv_heads=8] [d_ffn=28672]
+//
+// The second form runs the prompt-sized matrix-core projection (spec_dense_gemm) on the four layer shapes with
+// the epilogue the prefill path uses for each, and prints TFLOP/s.
 //
 // Used under `rocprofv3 --kernel-trace --stats` and `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE`.
 #include <hip/hip_runtime.h>
@@ -31,7 +35,54 @@
     }                                                                          \
   } while (0)
 
+static int dense_main(int argc, char** argv) {
+  const int M = argc > 2 ? atoi(argv[2]) : 4095;
+  const int iters = argc > 3 ? atoi(argv[3]) : 5;
+  const int d = argc > 4 ? atoi(argv[4]) : 8192;
+  const int hq = argc > 5 ? atoi(argv[5]) : 64;
+  const int hkv = argc > 6 ? atoi(argv[6]) : 8;
+  const int F = argc > 7 ? atoi(argv[7]) : 28672;
+  const int dh = d / hq;
+  struct Shape { const char* name; int N, K, epi; };
+  const Shape shapes[] = {{"qkv", (hq + 2 * hkv) * dh, d, 0}, {"o", d, hq * dh, 1}, {"gate_up", 2 * F, d, 2},
+                          {"down", d, F, 1}};
+  hipStream_t st;
+  CK(hipStreamCreate(&st));
+  size_t max_w = 0, max_x = 0, max_y = 0;
+  for (const Shape& s : shapes) {
+    if (spec_packed_bytes(s.N, s.K) > max_w) max_w = spec_packed_bytes(s.N, s.K);
+    if ((size_t)M * s.K * 2 > max_x) max_x = (size_t)M * s.K * 2;
+    if ((size_t)M * s.N * 4 > max_y) max_y = (size_t)M * s.N * 4;
+  }
+  void *w, *x, *y;
+  CK(hipMalloc(&w, max_w));
+  CK(hipMalloc(&x, max_x));
+  CK(hipMalloc(&y, max_y));
+  CK(hipMemset(w, 0x3c, max_w));
+  CK(hipMemset(x, 0x3c, max_x));
+  CK(hipMemset(y, 0, max_y));
+  CK(hipDeviceSynchronize());
+  hipEvent_t e0, e1;
+  CK(hipEventCreate(&e0));
+  CK(hipEventCreate(&e1));
+  printf("dense projection probe: M=%d, %d launches per shape\n", M, iters);
+  for (const Shape& s : shapes) {
+    SK(spec_dense_gemm((float*)y, y, x, w, M, s.N, s.K, s.epi, st));   // warm-up
+    CK(hipEventRecord(e0, st));
+    for (int i = 0; i < iters; ++i) SK(spec_dense_gemm((float*)y, y, x, w, M, s.N, s.K, s.epi, st));
+    CK(hipEventRecord(e1, st));
+    CK(hipStreamSynchronize(st));
+    float ms = 0.f;
+    CK(hipEventElapsedTime(&ms, e0, e1));
+    const double fl = 2.0 * M * s.N * s.K;
+    printf("  %-8s N=%6d K=%6d epilogue %d  %9.2f us  %7.1f TFLOP/s\n", s.name, s.N, s.K, s.epi, ms / iters * 1e3,
+           fl / (ms / iters * 1e-3) / 1e12);
+  }
+  return 0;
+}
+
 int main(int argc, char** argv) {
+  if (argc > 1 && argv[1][0] == 'd') return dense_main(argc, argv);
   const int M = argc > 1 ? atoi(argv[1]) : 7;
   const int iters = argc > 2 ? atoi(argv[2]) : 5;
   const int d = argc > 3 ? atoi(argv[3]) : 8192;

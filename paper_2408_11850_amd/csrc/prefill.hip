@@ -3,34 +3,26 @@
 // A prompt of C tokens goes through every projection as one dense GEMM Y[C][N] = X[C][K] W^T, so the
 // contraction has C flop per weight byte pair and belongs on the matrix cores at full tile size,
 // unlike the decode-time projections (<= 32 rows, HBM-bound).  W stays in the panel-packed order the decode
-// kernels stream (16 output rows x 32 k per 1 KiB block = one A operand of v_mfma_f32_16x16x32_bf16);
-// X is row-major bf16, and a 16-token x 32-k block of it gathered with one 16-byte load per lane is exactly
-// one B operand.  Both operand kinds are therefore moved global -> LDS with the LDS-direct loads of gfx950
-// (global_load_lds_dwordx4: lane l lands at base + 16 l, i.e. already in operand order) and read back with
-// one conflict-free ds_read_b128 per fragment.
+// kernels stream (16 output rows x 32 k per 1 KiB block = one A operand of v_mfma_f32_16x16x32_bf16), so a
+// wave loads its weight fragments straight from global memory into registers, three K steps ahead of their
+// use.  X is row-major bf16; a 16-token x 32-k block of it gathered with one 16-byte load per lane is exactly
+// one B operand, and since the four waves that share a token range all need it, it goes global -> LDS with the
+// LDS-direct loads of gfx950 (global_load_lds_dwordx4: lane l lands at base + 16 l, i.e. already in operand
+// order) and is read back with one conflict-free ds_read_b128 per fragment.  Keeping the weights out of LDS
+// matters: with both operands staged there the kernel was bound by LDS bandwidth.
 //
 // Tiling: workgroup = 8 waves = 256 tokens x 256 outputs, wave = 128 tokens x 64 outputs (8 x 4 MFMA tiles,
-// 128 accumulator registers, two waves per SIMD), K advances 32 per stage through a ring of DG_STAGES LDS
-// buffers of 32 KiB.
+// 128 accumulator registers, two waves per SIMD), K advances 32 per step; X steps go through a ring of
+// DG_STAGES LDS buffers of 16 KiB, W steps through a ring of DG_STAGES - 1 register sets.
 #include "spec_internal.h"
 
 #define DG_BM 256
 #define DG_BN 256
 #define DG_THREADS 512
 #define DG_STAGES 4
-#define DG_STAGE_U4 (32 * 64)          // 16-byte units per stage: 16 weight blocks + 16 activation blocks
+#define DG_STAGE_U4 (16 * 64)          // 16-byte units per LDS stage: 16 activation blocks
 
 enum { DG_EPI_STORE = 0, DG_EPI_RESID = 1, DG_EPI_SWIGLU = 2 };
-
-__device__ __forceinline__ void dg_issue_stage(const u32x4* __restrict__ wsrc[2], const bf16* __restrict__ xsrc[2],
-                                               u32x4* lds_stage, int w, int step) {
-#pragma unroll
-  for (int i = 0; i < 2; ++i)
-    __builtin_amdgcn_global_load_lds(wsrc[i] + (size_t)step * 64, lds_stage + (w * 2 + i) * 64, 16, 0, 0);
-#pragma unroll
-  for (int i = 0; i < 2; ++i)
-    __builtin_amdgcn_global_load_lds(xsrc[i] + (size_t)step * 32, lds_stage + (16 + w * 2 + i) * 64, 16, 0, 0);
-}
 
 // EPI: STORE  Y[m][n] = acc (fp32);  RESID  Y[m][n] += acc;  SWIGLU  Z[m][f] = silu(gate) * up (bf16) with the
 // gate / up panels interleaved (even panel = gate rows of f-tile j, odd = the matching up rows), N = 2F.
@@ -39,8 +31,8 @@ __global__ __launch_bounds__(DG_THREADS, 2) void dense_gemm_kernel(const bf16* _
                                                                    const u32x4* __restrict__ Wp,
                                                                    float* __restrict__ Y, bf16* __restrict__ Z, int M,
                                                                    int N, int K, int NT, int steps, int TM, int cx) {
-  extern __shared__ u32x4 lds[];
-  const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
+  __shared__ u32x4 lds[DG_STAGES * DG_STAGE_U4];
+  const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;   // w: wave-uniform
   // Workgroups are dealt to the 8 XCDs round-robin; XCD x owns tile columns [x cx, (x+1) cx) and walks them in
   // groups of 4 columns x all row tiles, so the 32 workgroups an XCD runs together share 8 x 4 operand strips
   // in its L2.
@@ -55,16 +47,24 @@ __global__ __launch_bounds__(DG_THREADS, 2) void dense_gemm_kernel(const bf16* _
   const int tm = idx / gw, tn = x * cx + grp * 4 + idx % gw;
 
   const int c = lane & 15, kb = lane >> 4;
-  const u32x4* wsrc[2];
-  const bf16* xsrc[2];
+  const int wn = w & 3, wm = w >> 2;      // wave grid: 4 along the outputs x 2 along the tokens
+  // Addresses are a wave-uniform base (scalar registers) plus a 32-bit per-lane offset, which keeps them out of
+  // the vector registers the accumulators and fragment rings need.
+  const char* wbase[4];                   // this wave's 4 weight panels (clamped rows are computed, never stored)
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    int panel = tn * 16 + wn * 4 + i;
+    if (panel > NT - 1) panel = NT - 1;
+    wbase[i] = reinterpret_cast<const char*>(Wp + (size_t)panel * steps * 64);
+  }
+  const unsigned woff = lane * 16;
+  const char* xbase = reinterpret_cast<const char*>(X);
+  unsigned xoff[2];                       // the 2 activation blocks this wave brings into every LDS stage
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
-    int panel = tn * 16 + w * 2 + i;
-    if (panel > NT - 1) panel = NT - 1;          // clamped rows are computed and never stored
-    wsrc[i] = Wp + (size_t)panel * steps * 64 + lane;
     int m = tm * DG_BM + (w * 2 + i) * 16 + c;
     if (m > M - 1) m = M - 1;
-    xsrc[i] = X + (size_t)m * K + kb * 8;
+    xoff[i] = (unsigned)m * (unsigned)K * 2u + kb * 16;     // < 2^32: checked by the launcher
   }
 
   f32x4 acc[4][8];
@@ -73,35 +73,88 @@ __global__ __launch_bounds__(DG_THREADS, 2) void dense_gemm_kernel(const bf16* _
 #pragma unroll
     for (int b = 0; b < 8; ++b) acc[a][b] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  // Pipeline: the LDS-direct loads of step ks + DG_STAGES - 1 are issued while step ks is multiplied.  Steps past
-  // the end reload the last step into a free buffer, which keeps the count of outstanding loads uniform.  The
-  // barrier is a bare s_barrier behind an explicit vmcnt wait: the fence of __syncthreads would drain every
-  // load in flight.
-#pragma unroll
-  for (int s = 0; s < DG_STAGES - 1; ++s)
-    dg_issue_stage(wsrc, xsrc, lds + s * DG_STAGE_U4, w, s < steps ? s : steps - 1);
-  const int wn = w & 3, wm = w >> 2;
-  const u32x4* fa = lds + (wn * 4) * 64 + lane;
-  const u32x4* fb = lds + (16 + wm * 8) * 64 + lane;
-  for (int ks = 0; ks < steps; ++ks) {
-    // this wave's 4 loads of stage ks have landed (8 younger ones may be in flight) ...
-    asm volatile("s_waitcnt vmcnt(8)\n\ts_barrier" ::: "memory");
-    // ... and so have everybody else's; all waves are also done reading stage ks - 1, whose buffer is refilled
-    const int nxt = ks + DG_STAGES - 1;
-    dg_issue_stage(wsrc, xsrc, lds + (nxt % DG_STAGES) * DG_STAGE_U4, w, nxt < steps ? nxt : steps - 1);
-    const int so = (ks % DG_STAGES) * DG_STAGE_U4;
-    bf16x8 a[4], b[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) b[i] = __builtin_bit_cast(bf16x8, fb[so + i * 64]);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) a[i] = __builtin_bit_cast(bf16x8, fa[so + i * 64]);
-#pragma unroll
-    for (int nt = 0; nt < 4; ++nt)
-#pragma unroll
-      for (int mt = 0; mt < 8; ++mt)
-        acc[nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[nt], b[mt], acc[nt][mt], 0, 0, 0);
+  // Every step issues 2 LDS-direct loads and 4 register loads per wave, in this order, DG_STAGES - 1 steps ahead.
+  // Steps past the end reload the last step (into a free buffer / a dead register set), which keeps the count
+  // of outstanding loads uniform so that one vmcnt threshold serves every iteration.
+  u32x4 wq[DG_STAGES - 1][4];
+#define DG_ISSUE(STEP, SET)                                                                                  \
+  {                                                                                                          \
+    const int st_ = (STEP) < steps ? (STEP) : steps - 1;                                                     \
+    u32x4* dst_ = lds + ((STEP) % DG_STAGES) * DG_STAGE_U4 + (w * 2) * 64;                                   \
+    const char* xs_ = xbase + (size_t)st_ * 64;                                                              \
+    __builtin_amdgcn_global_load_lds(xs_ + xoff[0], dst_, 16, 0, 0);                                         \
+    __builtin_amdgcn_global_load_lds(xs_ + xoff[1], dst_ + 64, 16, 0, 0);                                    \
+    _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                            \
+      asm volatile("global_load_dwordx4 %0, %1, %2"                                                          \
+                   : "=v"(wq[SET][i]) : "v"(woff), "s"(wbase[i] + (size_t)st_ * 1024) : "memory");           \
   }
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the redundant tail loads must not outlive the workgroup's LDS
+  // The weight loads are inline asm and the barrier is a bare s_barrier behind an explicit vmcnt wait, because
+  // the compiler's own bookkeeping would drain every load in flight (it orders nothing behind an LDS-direct
+  // load short of vmcnt(0), and so does the fence of __syncthreads).  The wait statement names the register set
+  // of the next step as read-write, which is what makes every use of those weights depend on it.
+  //
+  // One iteration = 32 MFMAs in two halves (tokens 0..63 and 64..127 of the wave's rows).  All 8 waves meet at
+  // one barrier per step, so the two waves of a SIMD run in phase and cannot hide each other's LDS latency;
+  // instead all activation fragments of step KS + 1 are read from LDS between the halves of step KS (the low
+  // half into the registers the first half has just consumed, the high half into a second set), so that their
+  // latency passes behind the 16 MFMAs of the second half.
+#define DG_ITER(KS, SET, NSET, HC, HN)                                                                       \
+  {                                                                                                          \
+    bf16x8 a[4];                                                                                             \
+    _Pragma("unroll") for (int i = 0; i < 4; ++i) a[i] = __builtin_bit_cast(bf16x8, wq[SET][i]);             \
+    _Pragma("unroll") for (int nt = 0; nt < 4; ++nt)                                                         \
+      _Pragma("unroll") for (int mt = 0; mt < 4; ++mt)                                                       \
+        acc[nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[nt], blo[mt], acc[nt][mt], 0, 0, 0);         \
+    __builtin_amdgcn_sched_barrier(0);                                                                       \
+    /* step KS+1: X is in LDS for all waves, this wave's weights are in wq[NSET] */                          \
+    asm volatile("s_waitcnt vmcnt(6)\n\ts_barrier"                                                            \
+                 : "+v"(wq[NSET][0]), "+v"(wq[NSET][1]), "+v"(wq[NSET][2]), "+v"(wq[NSET][3])::"memory");    \
+    const u32x4* fb = lds + (((KS) + 1) % DG_STAGES) * DG_STAGE_U4 + (wm * 8) * 64 + lane;                   \
+    _Pragma("unroll") for (int i = 0; i < 4; ++i) blo[i] = __builtin_bit_cast(bf16x8, fb[i * 64]);           \
+    _Pragma("unroll") for (int i = 0; i < 4; ++i) bhi[HN][i] = __builtin_bit_cast(bf16x8, fb[(4 + i) * 64]); \
+    __builtin_amdgcn_sched_barrier(0);                                                                       \
+    _Pragma("unroll") for (int nt = 0; nt < 4; ++nt)                                                         \
+      _Pragma("unroll") for (int mt = 0; mt < 4; ++mt)                                                       \
+        acc[nt][4 + mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[nt], bhi[HC][mt], acc[nt][4 + mt], 0, 0, 0); \
+    __builtin_amdgcn_sched_barrier(0);                                                                       \
+    DG_ISSUE((KS) + DG_STAGES - 1, SET)                                                                      \
+    __builtin_amdgcn_sched_barrier(0);                                                                       \
+  }
+  DG_ISSUE(0, 0)
+  DG_ISSUE(1, 1)
+  DG_ISSUE(2, 2)
+  bf16x8 blo[4], bhi[2][4];
+  asm volatile("s_waitcnt vmcnt(12)\n\ts_barrier"
+               : "+v"(wq[0][0]), "+v"(wq[0][1]), "+v"(wq[0][2]), "+v"(wq[0][3])::"memory");
+  {
+    const u32x4* fb = lds + (wm * 8) * 64 + lane;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      blo[i] = __builtin_bit_cast(bf16x8, fb[i * 64]);
+      bhi[0][i] = __builtin_bit_cast(bf16x8, fb[(4 + i) * 64]);
+    }
+  }
+  int ks = 0;
+  for (; ks + 6 <= steps; ks += 6) {
+    DG_ITER(ks, 0, 1, 0, 1)
+    DG_ITER(ks + 1, 1, 2, 1, 0)
+    DG_ITER(ks + 2, 2, 0, 0, 1)
+    DG_ITER(ks + 3, 0, 1, 1, 0)
+    DG_ITER(ks + 4, 1, 2, 0, 1)
+    DG_ITER(ks + 5, 2, 0, 1, 0)
+  }
+  if (ks < steps) DG_ITER(ks, 0, 1, 0, 1)
+  if (ks + 1 < steps) DG_ITER(ks + 1, 1, 2, 1, 0)
+  if (ks + 2 < steps) DG_ITER(ks + 2, 2, 0, 0, 1)
+  if (ks + 3 < steps) DG_ITER(ks + 3, 0, 1, 1, 0)
+  if (ks + 4 < steps) DG_ITER(ks + 4, 1, 2, 0, 1)
+#undef DG_ITER
+#undef DG_ISSUE
+  // The redundant tail loads must not outlive the workgroup's LDS, and their destination registers must not be
+  // handed to anything else while they are in flight: naming every set here keeps them allocated until now.
+  asm volatile("s_waitcnt vmcnt(0)"
+               : "+v"(wq[0][0]), "+v"(wq[0][1]), "+v"(wq[0][2]), "+v"(wq[0][3]), "+v"(wq[1][0]), "+v"(wq[1][1]),
+                 "+v"(wq[1][2]), "+v"(wq[1][3]), "+v"(wq[2][0]), "+v"(wq[2][1]), "+v"(wq[2][2]), "+v"(wq[2][3])::"memory");
 
   // acc[nt][mt][r] = Y[m0 + 16 mt + c][n0 + 16 nt + 4 kb + r]
   const int m0 = tm * DG_BM + wm * 128, n0 = tn * DG_BN + wn * 64;
@@ -135,35 +188,20 @@ __global__ __launch_bounds__(DG_THREADS, 2) void dense_gemm_kernel(const bf16* _
   }
 }
 
-size_t dense_gemm_lds_bytes() { return (size_t)DG_STAGES * DG_STAGE_U4 * 16; }
-
 hipError_t launch_dense_gemm(const bf16* x, const void* wp, int M, int N, int K, int epi, float* y, bf16* z,
                              hipStream_t st) {
-  static bool attr_set = false;
-  const size_t lds_bytes = dense_gemm_lds_bytes();
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)dense_gemm_kernel<DG_EPI_STORE>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-    if (e == hipSuccess)
-      e = hipFuncSetAttribute((const void*)dense_gemm_kernel<DG_EPI_RESID>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                              (int)lds_bytes);
-    if (e == hipSuccess)
-      e = hipFuncSetAttribute((const void*)dense_gemm_kernel<DG_EPI_SWIGLU>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                              (int)lds_bytes);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  if ((double)M * K * 2.0 >= 4294967296.0) return hipErrorInvalidValue;   // per-lane activation offsets are 32-bit
   const int NT = N / 16, steps = K / 32;
   const int TM = (M + DG_BM - 1) / DG_BM, TN = (NT + 15) / 16;
   const int cx = (TN + 7) / 8;
   const int groups = (cx + 3) / 4;
   dim3 grid(8 * groups * TM * 4), block(DG_THREADS);
   if (epi == DG_EPI_STORE)
-    dense_gemm_kernel<DG_EPI_STORE><<<grid, block, lds_bytes, st>>>(x, (const u32x4*)wp, y, z, M, N, K, NT, steps, TM, cx);
+    dense_gemm_kernel<DG_EPI_STORE><<<grid, block, 0, st>>>(x, (const u32x4*)wp, y, z, M, N, K, NT, steps, TM, cx);
   else if (epi == DG_EPI_RESID)
-    dense_gemm_kernel<DG_EPI_RESID><<<grid, block, lds_bytes, st>>>(x, (const u32x4*)wp, y, z, M, N, K, NT, steps, TM, cx);
+    dense_gemm_kernel<DG_EPI_RESID><<<grid, block, 0, st>>>(x, (const u32x4*)wp, y, z, M, N, K, NT, steps, TM, cx);
   else
-    dense_gemm_kernel<DG_EPI_SWIGLU><<<grid, block, lds_bytes, st>>>(x, (const u32x4*)wp, y, z, M, N, K, NT, steps, TM, cx);
+    dense_gemm_kernel<DG_EPI_SWIGLU><<<grid, block, 0, st>>>(x, (const u32x4*)wp, y, z, M, N, K, NT, steps, TM, cx);
   return hipGetLastError();
 }
 
