@@ -23,6 +23,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0      # dense bf16 matrix-core peak of the MI355X
 
 
 def parse():
@@ -182,8 +183,22 @@ def main():
     ctx = harness.make_context(cfg, target, draft, gamma_max, extra_seq=64)
     ctx.set_option(amd.SPEC_OPT_GEMM_WGS_PER_CU, args.wgs)
     prompt = synth.prompt_tokens(cfg.n_prompt, cfg.target.vocab, cfg.seed_prompt).tolist()
+    # prompt pass of each model alone (dense matrix-core path when the shapes allow it), then both for the run
+    def prefill_flops(sh, c):
+        per_layer = sh.d_model * (sh.n_heads + 2 * sh.n_kv_heads) * sh.head_dim + sh.n_heads * sh.head_dim * sh.d_model \
+            + 3 * sh.d_model * sh.d_ffn
+        return 2.0 * c * per_layer * sh.n_layers + 2.0 * sh.head_dim * sh.n_heads * c * c * sh.n_layers
+    ctx.prefill(prompt[:130], which_mask=3)            # first use allocates the prompt-path buffers
+    _, t_pf_t = timed(lambda: ctx.prefill(prompt, which_mask=1), sync)
+    _, t_pf_d = timed(lambda: ctx.prefill(prompt, which_mask=2), sync)
     _, t_prefill = timed(lambda: ctx.prefill(prompt), sync)
-    log(f"[bench] prefill of {cfg.n_prompt} tokens (both models): {t_prefill:.2f}s")
+    c_pf = cfg.n_prompt - 1
+    prefill_stats = {"tokens": c_pf, "target_s": t_pf_t, "draft_s": t_pf_d, "both_s": t_prefill,
+                     "target_TFLOPs": prefill_flops(cfg.target, c_pf) / t_pf_t / 1e12,
+                     "draft_TFLOPs": prefill_flops(cfg.draft, c_pf) / t_pf_d / 1e12, "bound": "mfma",
+                     "peak_TFLOPs": MFMA_BF16_PEAK_TFLOPS}
+    prefill_stats["target_frac_of_peak"] = prefill_stats["target_TFLOPs"] / MFMA_BF16_PEAK_TFLOPS
+    log(f"[bench] prefill of {cfg.n_prompt} tokens: {json.dumps({k: (round(v, 4) if isinstance(v, float) else v) for k, v in prefill_stats.items()})}")
     n0 = cfg.n_prompt
 
     # ---- window size: gamma = round(c), c = T(target forward) / T(draft forward) ---------------
@@ -310,6 +325,7 @@ def main():
                      "alone_achieved": gemm_alone, "alone_frac": gemm_alone / HBM_PEAK_GBS,
                      "alone_avg_launch_us": ms_a / max(n_a, 1) * 1e3},
         "pearl": pearl, "alone": alone_stats, "side": side,
+        "prefill": prefill_stats,
         "setup_s": {"build": t_build, "prefill": t_prefill},
     }
     if not args.no_cpu:

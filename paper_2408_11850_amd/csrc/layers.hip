@@ -120,17 +120,19 @@ hipError_t launch_addnorm(float* h, const float* partials, int S, const bf16* ga
   return hipGetLastError();
 }
 
-// One workgroup per (token, head) of the fused QKV output; thread e handles the pair (e, e + dh/2).
+// One 64-thread slice of a workgroup per (token, head) of the fused QKV output (ROPE_HPB heads per workgroup);
+// thread e of the slice handles the pair (e, e + dh/2).
 // q heads: rotate, store bf16 [M][Hq][dh].  k heads: rotate, store into the page in K-operand order.
 // v heads: store into the page in V-operand order.  Position of token i is len + i.
+#define ROPE_HPB 4
 __global__ void rope_append_kernel(const float* __restrict__ P, int S, bf16* __restrict__ q, bf16* __restrict__ pool,
                                    const int* __restrict__ block_table, const int* __restrict__ len_ptr, KvGeom g,
                                    int layer, int M, int Hq, float theta) {
-  const int i = blockIdx.x, head = blockIdx.y;
+  const int i = blockIdx.x, head = blockIdx.y * ROPE_HPB + (threadIdx.x >> 6);
   const int dh = g.head_dim, half = dh >> 1, Hkv = g.n_kv_heads;
   const int N = (Hq + 2 * Hkv) * dh;
-  const int e = threadIdx.x;
-  if (e >= half) return;
+  const int e = threadIdx.x & 63;
+  if (e >= half || head >= Hq + 2 * Hkv) return;
   const int pos = len_ptr[0] + i;
   float x0 = 0.f, x1 = 0.f;
   for (int s = 0; s < S; ++s) {
@@ -170,7 +172,7 @@ __global__ void rope_append_kernel(const float* __restrict__ P, int S, bf16* __r
 }
 hipError_t launch_rope_append(const float* partials, int S, bf16* q, bf16* pool, const int* block_table,
                               const int* len_ptr, KvGeom g, int layer, int M, int Hq, float theta, hipStream_t st) {
-  dim3 grid(M, Hq + 2 * g.n_kv_heads), block(64);
+  dim3 grid(M, (Hq + 2 * g.n_kv_heads + ROPE_HPB - 1) / ROPE_HPB), block(64 * ROPE_HPB);
   rope_append_kernel<<<grid, block, 0, st>>>(partials, S, q, pool, block_table, len_ptr, g, layer, M, Hq, theta);
   return hipGetLastError();
 }

@@ -208,32 +208,31 @@ hipError_t launch_dense_gemm(const bf16* x, const void* wp, int M, int N, int K,
 // ---------------------------------------------------------------------------------------------------------
 // Causal attention of a block of M prompt tokens over the paged KV cache (positions 0 .. len + M - 1, the
 // block's own K / V already appended).  Rows are the M*G (token, query head) pairs of one KV head, token-major,
-// as in the decode kernel; a workgroup of 4 waves owns 256 consecutive rows, a wave 4 tiles of 16.  K and V
-// pages are in MFMA operand order, so every 32-position chunk is 16 KiB (head_dim 128) that the workgroup
-// brings into LDS once with LDS-direct loads and each wave reads as ready-made fragments: S^T = K Q^T,
-// online softmax per query row, O^T += V^T P^T.  Chunks beyond the last position a workgroup's rows may see
-// are never touched (causal skip), and the workgroups with the longest ranges are scheduled first.
+// as in the decode kernel; a workgroup of 8 waves owns 256 consecutive rows, a wave 2 tiles of 16 (two waves
+// per SIMD, so that one wave's softmax arithmetic overlaps the other's MFMAs).  K and V pages are in MFMA
+// operand order, so every 64-position chunk (= one page) is 32 KiB (head_dim 128) that the workgroup brings
+// into LDS once with LDS-direct loads and each wave reads as ready-made fragments: S^T = K Q^T, online softmax
+// per query row in the base-2 domain, O^T += V^T P^T.  Chunks beyond the last position a workgroup's rows may
+// see are never touched (causal skip), and the workgroups with the longest ranges are scheduled first.
 // ---------------------------------------------------------------------------------------------------------
-#define PA_WAVES 4
-#define PA_QT 4                                  // 16-row tiles per wave
+#define PA_WAVES 8
+#define PA_QT 2                                  // 16-row tiles per wave
 #define PA_ROWS (PA_WAVES * PA_QT * 16)          // rows per workgroup
-#define PA_STAGES 3
+#define PA_STAGES 2
 #define PA_NEG_BIG (-1.0e30f)
 
-// Brings chunk `ch` (32 positions) of one KV head into an LDS stage.  Block b of a chunk: b < KB -> K block b
-// (lane-linear in the page), else V block b - KB, whose lane (c, g4) sits at byte c*64 + g4*16 of the block.
+// Brings chunk `ch` (64 positions = page block_table[ch]) of one KV head into an LDS stage.  Block b of a chunk:
+// b < KB -> K block b (lane-linear in the page), else V block b - KB, whose lane (c, g4) sits at byte
+// c*64 + g4*16 of the block.
 template <int DH>
 __device__ __forceinline__ void pa_issue(const bf16* __restrict__ pool, const int* __restrict__ block_table,
                                          const KvGeom& g, int layer, int kvh, int ch, u32x4* lds_stage, int w,
                                          int lane) {
-  constexpr int KB = 2 * (DH / 32), VB = DH / 16, LPW = (KB + VB) / PA_WAVES;
+  constexpr int KB = 4 * (DH / 32), VB = 2 * (DH / 16), LPW = (KB + VB) / PA_WAVES;
   const int c = lane & 15, g4 = lane >> 4;
-  const int pos0 = ch << 5;
-  const int page = block_table[pos0 / SPEC_PAGE_TOKENS];
-  const int inpage = pos0 % SPEC_PAGE_TOKENS;
-  const u32x4* kblk = reinterpret_cast<const u32x4*>(pool + g.offset(page, layer, 0, kvh)) +
-                      (size_t)(inpage >> 4) * (DH / 32) * 64 + lane;
-  const bf16* vblk = pool + g.offset(page, layer, 1, kvh) + (size_t)(inpage >> 5) * DH * 32;
+  const int page = block_table[ch];
+  const u32x4* kblk = reinterpret_cast<const u32x4*>(pool + g.offset(page, layer, 0, kvh)) + lane;
+  const bf16* vblk = pool + g.offset(page, layer, 1, kvh);
 #pragma unroll
   for (int i = 0; i < LPW; ++i) {
     const int b = w * LPW + i;
@@ -244,50 +243,51 @@ __device__ __forceinline__ void pa_issue(const bf16* __restrict__ pool, const in
 }
 
 template <int DH>
-__global__ __launch_bounds__(PA_WAVES * 64, 1) void prefill_attn_kernel(const bf16* __restrict__ q,
+__global__ __launch_bounds__(PA_WAVES * 64, 2) void prefill_attn_kernel(const bf16* __restrict__ q,
                                                                         const bf16* __restrict__ pool,
                                                                         const int* __restrict__ block_table,
                                                                         const int* __restrict__ len_ptr, KvGeom g,
-                                                                        int layer, int M, int Hq, float scale,
+                                                                        int layer, int M, int Hq, float scale_log2e,
                                                                         bf16* __restrict__ out) {
-  constexpr int KB = 2 * (DH / 32);              // K blocks (1 KiB) per chunk
-  constexpr int VB = DH / 16;                    // V blocks per chunk
+  constexpr int KS = DH / 32;                    // K steps per 16-position tile
+  constexpr int KB = 4 * KS;                     // K blocks (1 KiB) per chunk
+  constexpr int VB = 2 * (DH / 16);              // V blocks per chunk
   constexpr int NB = KB + VB;
-  constexpr int LPW = NB / PA_WAVES;             // LDS-direct loads per wave and chunk
   __shared__ u32x4 lds[PA_STAGES][NB][64];
   const int kvh = blockIdx.y;
   const int rb = gridDim.x - 1 - blockIdx.x;     // longest ranges first
-  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int c = lane & 15, g4 = lane >> 4;
   const int Hkv = g.n_kv_heads, G = Hq / Hkv, R = M * G;
   const int len = len_ptr[0];
   const int r0 = rb * PA_ROWS;
   int rlast = r0 + PA_ROWS - 1;
   if (rlast > R - 1) rlast = R - 1;
-  const int nch = ((len + rlast / G) >> 5) + 1;  // chunks this workgroup needs
+  const int nch = ((len + rlast / G) >> 6) + 1;  // chunks this workgroup needs
   int wlast = r0 + (w + 1) * PA_QT * 16 - 1;
   if (wlast > R - 1) wlast = R - 1;
   const int wave_limit = (r0 + w * PA_QT * 16 < R) ? len + wlast / G : -1;
 
-  // per q tile: row of this lane, its visibility limit and its Q fragments
+  // per q tile: row of this lane, its visibility limit and its Q fragments.  Rows past the end behave like
+  // unmasked rows of zeros (finite arithmetic, never stored).
   int limit[PA_QT];
-  bf16x8 qf[PA_QT][DH / 32];
+  bf16x8 qf[PA_QT][KS];
 #pragma unroll
   for (int t = 0; t < PA_QT; ++t) {
     const int Rr = r0 + (w * PA_QT + t) * 16 + c;
     const bool valid = Rr < R;
     const int tok = valid ? Rr / G : 0;
     const int head = kvh * G + (valid ? Rr % G : 0);
-    limit[t] = valid ? len + tok : -1;
+    limit[t] = valid ? len + tok : 0x7fffffff;
 #pragma unroll
-    for (int j = 0; j < DH / 32; ++j) {
+    for (int j = 0; j < KS; ++j) {
       u32x4 v = {0u, 0u, 0u, 0u};
       if (valid) v = *reinterpret_cast<const u32x4*>(q + ((size_t)tok * Hq + head) * DH + j * 32 + g4 * 8);
       qf[t][j] = __builtin_bit_cast(bf16x8, v);
     }
   }
 
-  float m_run[PA_QT], l_run[PA_QT];
+  float m_run[PA_QT], l_run[PA_QT];             // running max (base-2 domain) and sum per query row
   f32x4 o[PA_QT][DH / 16];
 #pragma unroll
   for (int t = 0; t < PA_QT; ++t) {
@@ -298,67 +298,72 @@ __global__ __launch_bounds__(PA_WAVES * 64, 1) void prefill_attn_kernel(const bf
   }
 
   pa_issue<DH>(pool, block_table, g, layer, kvh, 0, &lds[0][0][0], w, lane);
-  pa_issue<DH>(pool, block_table, g, layer, kvh, nch > 1 ? 1 : 0, &lds[1][0][0], w, lane);
   for (int ch = 0; ch < nch; ++ch) {
-    // stage ch has landed for this wave (one younger stage may be in flight), then for everybody
-    if (LPW == 4) asm volatile("s_waitcnt vmcnt(4)\n\ts_barrier" ::: "memory");
-    else asm volatile("s_waitcnt vmcnt(2)\n\ts_barrier" ::: "memory");
-    pa_issue<DH>(pool, block_table, g, layer, kvh, ch + 2 < nch ? ch + 2 : nch - 1, &lds[(ch + 2) % PA_STAGES][0][0], w,
+    // chunk ch has landed for this wave, then for everybody; all waves are done with the other stage
+    asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+    pa_issue<DH>(pool, block_table, g, layer, kvh, ch + 1 < nch ? ch + 1 : nch - 1, &lds[(ch + 1) % PA_STAGES][0][0], w,
                  lane);
-    const int pos0 = ch << 5;
+    const int pos0 = ch << 6;
     if (pos0 > wave_limit) continue;           // nothing visible for this wave's rows (uniform per wave)
-    const int stg = ch % PA_STAGES;
-    bf16x8 kf[2][DH / 32], vf[DH / 16];
-#pragma unroll
-    for (int t2 = 0; t2 < 2; ++t2)
-#pragma unroll
-      for (int j = 0; j < DH / 32; ++j) kf[t2][j] = __builtin_bit_cast(bf16x8, lds[stg][t2 * (DH / 32) + j][lane]);
-#pragma unroll
-    for (int dt = 0; dt < DH / 16; ++dt) vf[dt] = __builtin_bit_cast(bf16x8, lds[stg][KB + dt][lane]);
+    const u32x4(*st)[64] = lds[ch % PA_STAGES];
 
+    // scores of the 64 positions: s[t][t4][r] = position pos0 + 16 t4 + 4 g4 + r for query row c of tile t
+    f32x4 s[PA_QT][4];
+#pragma unroll
+    for (int t4 = 0; t4 < 4; ++t4) {
+      bf16x8 kf[KS];
+#pragma unroll
+      for (int j = 0; j < KS; ++j) kf[j] = __builtin_bit_cast(bf16x8, st[t4 * KS + j][lane]);
+#pragma unroll
+      for (int t = 0; t < PA_QT; ++t) {
+        s[t][t4] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int j = 0; j < KS; ++j)
+          s[t][t4] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[j], qf[t][j], s[t][t4], 0, 0, 0);
+      }
+    }
+    bf16x8 pf[PA_QT][2];                        // P fragments of the two 32-position halves
 #pragma unroll
     for (int t = 0; t < PA_QT; ++t) {
-      f32x4 s[2];
-#pragma unroll
-      for (int t2 = 0; t2 < 2; ++t2) {
-        s[t2] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int j = 0; j < DH / 32; ++j)
-          s[t2] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[t2][j], qf[t][j], s[t2], 0, 0, 0);
-      }
-      // s[t2][r] = score of position pos0 + 16 t2 + 4 g4 + r for query row c of tile t
       float mx = PA_NEG_BIG;
 #pragma unroll
-      for (int t2 = 0; t2 < 2; ++t2)
+      for (int t4 = 0; t4 < 4; ++t4)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-          const int pos = pos0 + t2 * 16 + g4 * 4 + r;
-          const float v = (pos <= limit[t]) ? s[t2][r] * scale : PA_NEG_BIG;
-          s[t2][r] = v;
+          const int pos = pos0 + t4 * 16 + g4 * 4 + r;
+          const float v = (pos <= limit[t]) ? s[t][t4][r] * scale_log2e : PA_NEG_BIG;
+          s[t][t4][r] = v;
           mx = fmaxf(mx, v);
         }
       mx = fmaxf(mx, __shfl_xor(mx, 16));
       mx = fmaxf(mx, __shfl_xor(mx, 32));
+      // position 0 is visible to every row, so after the first chunk the running max is a real score and a
+      // masked entry (-1e30) underflows to exactly 0
       const float m_new = fmaxf(m_run[t], mx);
-      const float corr = __expf(m_run[t] - m_new);
+      const float corr = __builtin_amdgcn_exp2f(m_run[t] - m_new);
       float psum = 0.f;
-      bf16x8 pf;
 #pragma unroll
-      for (int t2 = 0; t2 < 2; ++t2)
+      for (int t4 = 0; t4 < 4; ++t4)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-          const float p = (s[t2][r] > 0.5f * PA_NEG_BIG) ? __expf(s[t2][r] - m_new) : 0.f;
-          psum += p;
-          pf[t2 * 4 + r] = (__bf16)p;
+          const float pv = __builtin_amdgcn_exp2f(s[t][t4][r] - m_new);
+          psum += pv;
+          pf[t][t4 >> 1][(t4 & 1) * 4 + r] = (__bf16)pv;
         }
       l_run[t] = l_run[t] * corr + psum;
       m_run[t] = m_new;
 #pragma unroll
-      for (int dt = 0; dt < DH / 16; ++dt) {
-        o[t][dt] *= corr;
-        o[t][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[dt], pf, o[t][dt], 0, 0, 0);
-      }
+      for (int dt = 0; dt < DH / 16; ++dt) o[t][dt] *= corr;
     }
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+      for (int dt = 0; dt < DH / 16; ++dt) {
+        const bf16x8 vf = __builtin_bit_cast(bf16x8, st[KB + h * (DH / 16) + dt][lane]);
+#pragma unroll
+        for (int t = 0; t < PA_QT; ++t)
+          o[t][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[t][h], o[t][dt], 0, 0, 0);
+      }
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the redundant tail loads must not outlive the workgroup's LDS
 
@@ -386,10 +391,10 @@ hipError_t launch_prefill_attention(const bf16* q, const bf16* pool, const int* 
                                     KvGeom g, int layer, int M, int Hq, bf16* out, hipStream_t st) {
   const int Hkv = g.n_kv_heads, G = Hq / Hkv, R = M * G, dh = g.head_dim;
   dim3 grid((R + PA_ROWS - 1) / PA_ROWS, Hkv), block(PA_WAVES * 64);
-  const float scale = 1.0f / sqrtf((float)dh);
+  const float scale_log2e = 1.4426950408889634f / sqrtf((float)dh);
   if (dh == 128)
-    prefill_attn_kernel<128><<<grid, block, 0, st>>>(q, pool, block_table, len_ptr, g, layer, M, Hq, scale, out);
+    prefill_attn_kernel<128><<<grid, block, 0, st>>>(q, pool, block_table, len_ptr, g, layer, M, Hq, scale_log2e, out);
   else
-    prefill_attn_kernel<64><<<grid, block, 0, st>>>(q, pool, block_table, len_ptr, g, layer, M, Hq, scale, out);
+    prefill_attn_kernel<64><<<grid, block, 0, st>>>(q, pool, block_table, len_ptr, g, layer, M, Hq, scale_log2e, out);
   return hipGetLastError();
 }
