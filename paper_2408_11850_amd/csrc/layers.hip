@@ -125,9 +125,23 @@ hipError_t launch_addnorm(float* h, const float* partials, int S, const bf16* ga
 // q heads: rotate, store bf16 [M][Hq][dh].  k heads: rotate, store into the page in K-operand order.
 // v heads: store into the page in V-operand order.  Position of token i is len + i.
 #define ROPE_HPB 4
+// (cos, sin) of the rotation angle of pair e at position len + i, for all tokens of a prompt block: the same
+// expression as in rope_append_kernel, evaluated once per block instead of once per layer and head.
+__global__ void rope_table_kernel(float2* __restrict__ tab, const int* __restrict__ len_ptr, int dh, float theta) {
+  const int i = blockIdx.x, e = threadIdx.x, half = dh >> 1;
+  if (e >= half) return;
+  const int pos = len_ptr[0] + i;
+  const double ang = (double)pos * pow((double)theta, -2.0 * (double)e / (double)dh);
+  tab[(size_t)i * half + e] = make_float2((float)cos(ang), (float)sin(ang));
+}
+hipError_t launch_rope_table(float2* tab, const int* len_ptr, int M, int dh, float theta, hipStream_t st) {
+  rope_table_kernel<<<M, 64, 0, st>>>(tab, len_ptr, dh, theta);
+  return hipGetLastError();
+}
+
 __global__ void rope_append_kernel(const float* __restrict__ P, int S, bf16* __restrict__ q, bf16* __restrict__ pool,
                                    const int* __restrict__ block_table, const int* __restrict__ len_ptr, KvGeom g,
-                                   int layer, int M, int Hq, float theta) {
+                                   int layer, int M, int Hq, float theta, const float2* __restrict__ tab) {
   const int i = blockIdx.x, head = blockIdx.y * ROPE_HPB + (threadIdx.x >> 6);
   const int dh = g.head_dim, half = dh >> 1, Hkv = g.n_kv_heads;
   const int N = (Hq + 2 * Hkv) * dh;
@@ -141,8 +155,14 @@ __global__ void rope_append_kernel(const float* __restrict__ P, int S, bf16* __r
     x1 += row[e + half];
   }
   if (head < Hq + Hkv) {   // rotate pair (e, e + dh/2) by pos * theta^(-2e/dh)
-    const double ang = (double)pos * pow((double)theta, -2.0 * (double)e / (double)dh);
-    const float cs = (float)cos(ang), sn = (float)sin(ang);
+    float cs, sn;
+    if (tab) {
+      const float2 t = tab[(size_t)i * half + e];
+      cs = t.x; sn = t.y;
+    } else {
+      const double ang = (double)pos * pow((double)theta, -2.0 * (double)e / (double)dh);
+      cs = (float)cos(ang); sn = (float)sin(ang);
+    }
     const float y0 = x0 * cs - x1 * sn, y1 = x0 * sn + x1 * cs;
     x0 = y0; x1 = y1;
   }
@@ -171,9 +191,10 @@ __global__ void rope_append_kernel(const float* __restrict__ P, int S, bf16* __r
   }
 }
 hipError_t launch_rope_append(const float* partials, int S, bf16* q, bf16* pool, const int* block_table,
-                              const int* len_ptr, KvGeom g, int layer, int M, int Hq, float theta, hipStream_t st) {
+                              const int* len_ptr, KvGeom g, int layer, int M, int Hq, float theta, hipStream_t st,
+                              const float2* tab) {
   dim3 grid(M, (Hq + 2 * g.n_kv_heads + ROPE_HPB - 1) / ROPE_HPB), block(64 * ROPE_HPB);
-  rope_append_kernel<<<grid, block, 0, st>>>(partials, S, q, pool, block_table, len_ptr, g, layer, M, Hq, theta);
+  rope_append_kernel<<<grid, block, 0, st>>>(partials, S, q, pool, block_table, len_ptr, g, layer, M, Hq, theta, tab);
   return hipGetLastError();
 }
 

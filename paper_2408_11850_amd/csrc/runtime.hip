@@ -61,6 +61,7 @@ struct ModelRt {
   int* pf_tok = nullptr;
   float *pf_h = nullptr, *pf_y = nullptr;
   bf16 *pf_a = nullptr, *pf_q = nullptr, *pf_attn = nullptr, *pf_z = nullptr;
+  float2* pf_rope = nullptr;      // (cos, sin) per token and rotation pair of the current block
 };
 
 struct ProfEvents {
@@ -184,7 +185,7 @@ void free_model(ModelRt& m) {
           g = nullptr;
         }
   void* ptrs[] = {m.pool, m.block_table_dev, m.len_dev, m.tok_in, m.h, m.a, m.qbuf, m.attn_out, m.z, m.partials,
-                  m.opart, m.logits, m.pf_tok, m.pf_h, m.pf_y, m.pf_a, m.pf_q, m.pf_attn, m.pf_z};
+                  m.opart, m.logits, m.pf_tok, m.pf_h, m.pf_y, m.pf_a, m.pf_q, m.pf_attn, m.pf_z, m.pf_rope};
   for (void* p : ptrs)
     if (p) (void)hipFree(p);
 }
@@ -343,6 +344,7 @@ int ensure_prefill_buffers(ModelRt& m) {
   if ((rc = dev_alloc(&m.pf_q, C * HD))) return rc;
   if ((rc = dev_alloc(&m.pf_attn, C * HD))) return rc;
   if ((rc = dev_alloc(&m.pf_z, C * d.d_ffn))) return rc;
+  if ((rc = dev_alloc(&m.pf_rope, C * (d.head_dim / 2)))) return rc;
   m.pf_cap = cap;
   return SPEC_OK;
 }
@@ -357,13 +359,14 @@ int prefill_dense_block(spec_ctx* c, int which, const int32_t* tok, int C) {
   if ((rc = ensure_pages(m, m.len + C))) return rc;
   HIPCHK(hipMemcpyAsync(m.pf_tok, tok, (size_t)C * sizeof(int), hipMemcpyHostToDevice, st));
   HIPCHK(launch_embed(m.pf_h, (const bf16*)m.tok_embed, m.pf_tok, C, d.d_model, d.vocab, st));
+  HIPCHK(launch_rope_table(m.pf_rope, m.len_dev, C, d.head_dim, d.rope_theta, st));
   const int qkvN = (d.n_heads + 2 * d.n_kv_heads) * d.head_dim;
   const int HD = d.n_heads * d.head_dim;
   for (int l = 0; l < d.n_layers; ++l) {
     HIPCHK(launch_addnorm(m.pf_h, nullptr, 0, (const bf16*)m.attn_norm[l], m.pf_a, C, d.d_model, d.rms_eps, st));
     HIPCHK(launch_dense_gemm(m.pf_a, m.wqkv[l], C, qkvN, d.d_model, 0, m.pf_y, nullptr, st));
     HIPCHK(launch_rope_append(m.pf_y, 1, m.pf_q, m.pool, m.block_table_dev, m.len_dev, m.geom, l, C, d.n_heads,
-                              d.rope_theta, st));
+                              d.rope_theta, st, m.pf_rope));
     HIPCHK(launch_prefill_attention(m.pf_q, m.pool, m.block_table_dev, m.len_dev, m.geom, l, C, d.n_heads, m.pf_attn,
                                     st));
     HIPCHK(launch_dense_gemm(m.pf_attn, m.wo[l], C, d.d_model, HD, 1, m.pf_h, nullptr, st));

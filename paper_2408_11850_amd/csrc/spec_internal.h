@@ -74,8 +74,11 @@ hipError_t launch_embed(float* h, const bf16* embed, const int* tok, int M, int 
 // h += sum_s partials[s] (if partials), a = rmsnorm(h) * gain
 hipError_t launch_addnorm(float* h, const float* partials, int S, const bf16* gain, bf16* a, int M, int d,
                           float eps, hipStream_t st);
+// tab: optional [M][dh/2] (cos, sin) table from launch_rope_table for the same len; nullptr = compute in place
 hipError_t launch_rope_append(const float* partials, int S, bf16* q, bf16* pool, const int* block_table,
-                              const int* len_ptr, KvGeom g, int layer, int M, int Hq, float theta, hipStream_t st);
+                              const int* len_ptr, KvGeom g, int layer, int M, int Hq, float theta, hipStream_t st,
+                              const float2* tab = nullptr);
+hipError_t launch_rope_table(float2* tab, const int* len_ptr, int M, int dh, float theta, hipStream_t st);
 hipError_t launch_attention(const bf16* q, const bf16* pool, const int* block_table, const int* len_ptr, KvGeom g,
                             int layer, int M, int Hq, int split_tokens, float* opart, float* mlpart, bf16* out,
                             hipStream_t st);
