@@ -3,35 +3,45 @@
 // A prompt of C tokens goes through every projection as one dense GEMM Y[C][N] = X[C][K] W^T, so the
 // contraction has C flop per weight byte pair and belongs on the matrix cores at full tile size,
 // unlike the decode-time projections (<= 32 rows, HBM-bound).  W stays in the panel-packed order the decode
-// kernels stream (16 output rows x 32 k per 1 KiB block = one A operand of v_mfma_f32_16x16x32_bf16), so a
-// wave loads its weight fragments straight from global memory into registers, three K steps ahead of their
-// use.  X is row-major bf16; a 16-token x 32-k block of it gathered with one 16-byte load per lane is exactly
-// one B operand, and since the four waves that share a token range all need it, it goes global -> LDS with the
-// LDS-direct loads of gfx950 (global_load_lds_dwordx4: lane l lands at base + 16 l, i.e. already in operand
-// order) and is read back with one conflict-free ds_read_b128 per fragment.  Keeping the weights out of LDS
-// matters: with both operands staged there the kernel was bound by LDS bandwidth.
+// kernels stream (16 output rows x 32 k per 1 KiB block = one A operand of v_mfma_f32_16x16x32_bf16); X is
+// row-major bf16, and a 16-token x 32-k block of it gathered with one 16-byte load per lane is exactly one
+// B operand.
 //
-// Tiling: workgroup = 8 waves = 256 tokens x 256 outputs, wave = 128 tokens x 64 outputs (8 x 4 MFMA tiles,
-// 128 accumulator registers, two waves per SIMD), K advances 32 per step; X steps go through a ring of
-// DG_STAGES LDS buffers of 16 KiB, W steps through a ring of DG_STAGES - 1 register sets.
+// Tiling: workgroup = 4 waves (one per SIMD, 512 registers each) = 256 tokens x 256 outputs; wave w owns the
+// outputs 64 w .. 64 w + 63 for all 256 tokens: 4 x 16 MFMA tiles whose 256 accumulator registers fill the
+// AGPR file.  Measured on this part, a CU moves about 25 bytes per clock from L2 and about 62 from LDS, so the
+// tile is built to need the least of both per MFMA:
+//   * every weight fragment is used by exactly one wave, which loads it straight from global memory into
+//     registers three K steps ahead (no LDS traffic, no duplicate loads), through a ring of four register sets;
+//   * X is needed by all four waves and goes global -> LDS once per workgroup with the LDS-direct loads of
+//     gfx950 (global_load_lds_dwordx4: lane l lands at base + 16 l, i.e. already in operand order); a wave
+//     reads each of its 16 fragments back with one conflict-free ds_read_b128.
+// Per 32-wide K step that is 32 KiB from L2 and 80 KiB through LDS for 64 MFMAs per wave (1024 MFMA cycles).
+//
+// The inner loop is inline asm with hand-placed waits.  The compiler cannot be trusted with it: it drains every
+// load in flight behind an LDS-direct load (vmcnt(0)), shuffles accumulators between register files when all
+// 256 AGPRs are live, and sinks LDS reads to just before their use.  Every asm statement names the registers
+// it defines or that a wait makes valid, so the compiler still sees all data flow.
 #include "spec_internal.h"
 
 #define DG_BM 256
 #define DG_BN 256
-#define DG_THREADS 512
-#define DG_STAGES 4
-#define DG_STAGE_U4 (16 * 64)          // 16-byte units per LDS stage: 16 activation blocks
+#define DG_THREADS 256
+#define DG_STAGES 4                    // LDS ring of X steps
+#define DG_STAGE_BYTES 16384           // 16 activation blocks of 1 KiB
 
 enum { DG_EPI_STORE = 0, DG_EPI_RESID = 1, DG_EPI_SWIGLU = 2 };
+
+typedef __attribute__((address_space(3))) u32x4 dg_lds_u32x4;
 
 // EPI: STORE  Y[m][n] = acc (fp32);  RESID  Y[m][n] += acc;  SWIGLU  Z[m][f] = silu(gate) * up (bf16) with the
 // gate / up panels interleaved (even panel = gate rows of f-tile j, odd = the matching up rows), N = 2F.
 template <int EPI>
-__global__ __launch_bounds__(DG_THREADS, 2) void dense_gemm_kernel(const bf16* __restrict__ X,
+__global__ __launch_bounds__(DG_THREADS, 1) void dense_gemm_kernel(const bf16* __restrict__ X,
                                                                    const u32x4* __restrict__ Wp,
                                                                    float* __restrict__ Y, bf16* __restrict__ Z, int M,
                                                                    int N, int K, int NT, int steps, int TM, int cx) {
-  __shared__ u32x4 lds[DG_STAGES * DG_STAGE_U4];
+  __shared__ u32x4 lds[DG_STAGES * DG_STAGE_BYTES / 16];
   const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;   // w: wave-uniform
   // Workgroups are dealt to the 8 XCDs round-robin; XCD x owns tile columns [x cx, (x+1) cx) and walks them in
   // groups of 4 columns x all row tiles, so the 32 workgroups an XCD runs together share 8 x 4 operand strips
@@ -47,119 +57,114 @@ __global__ __launch_bounds__(DG_THREADS, 2) void dense_gemm_kernel(const bf16* _
   const int tm = idx / gw, tn = x * cx + grp * 4 + idx % gw;
 
   const int c = lane & 15, kb = lane >> 4;
-  const int wn = w & 3, wm = w >> 2;      // wave grid: 4 along the outputs x 2 along the tokens
-  // Addresses are a wave-uniform base (scalar registers) plus a 32-bit per-lane offset, which keeps them out of
-  // the vector registers the accumulators and fragment rings need.
+  // Addresses are a wave-uniform base (scalar registers) plus a 32-bit per-lane offset.
   const char* wbase[4];                   // this wave's 4 weight panels (clamped rows are computed, never stored)
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    int panel = tn * 16 + wn * 4 + i;
+    int panel = tn * 16 + w * 4 + i;
     if (panel > NT - 1) panel = NT - 1;
     wbase[i] = reinterpret_cast<const char*>(Wp + (size_t)panel * steps * 64);
   }
   const unsigned woff = lane * 16;
   const char* xbase = reinterpret_cast<const char*>(X);
-  unsigned xoff[2];                       // the 2 activation blocks this wave brings into every LDS stage
+  unsigned xoff[4];                       // the 4 activation blocks this wave brings into every LDS stage
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    int m = tm * DG_BM + (w * 2 + i) * 16 + c;
+  for (int i = 0; i < 4; ++i) {
+    int m = tm * DG_BM + (w * 4 + i) * 16 + c;
     if (m > M - 1) m = M - 1;
     xoff[i] = (unsigned)m * (unsigned)K * 2u + kb * 16;     // < 2^32: checked by the launcher
   }
+  const unsigned lds_rd = (unsigned)(size_t)(dg_lds_u32x4*)lds + lane * 16;   // LDS byte address of this lane's slot
 
-  f32x4 acc[4][8];
+  f32x4 acc[4][16];
 #pragma unroll
   for (int a = 0; a < 4; ++a)
 #pragma unroll
-    for (int b = 0; b < 8; ++b) acc[a][b] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int b = 0; b < 16; ++b) acc[a][b] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  // Every step issues 2 LDS-direct loads and 4 register loads per wave, in this order, DG_STAGES - 1 steps ahead.
-  // Steps past the end reload the last step (into a free buffer / a dead register set), which keeps the count
-  // of outstanding loads uniform so that one vmcnt threshold serves every iteration.
-  u32x4 wq[DG_STAGES - 1][4];
-#define DG_ISSUE(STEP, SET)                                                                                  \
+  // Load schedule per wave: iteration j issues the 4 LDS-direct loads of X step j+3 and the 4 register loads of
+  // W step j+3, alternating, one after every second token tile, i.e. 8 MFMAs apart: the address unit takes
+  // about 30 cycles per 1 KiB wave load, and a wave that issues loads back to back sits in the issue stage
+  // (issuing no MFMAs) until the unit has taken them all.  Vector-memory operations complete in order.  Steps past
+  // the end reload the last step (into a free buffer / a dead register set), which keeps the count of
+  // outstanding loads uniform so that one vmcnt threshold serves every iteration.
+  u32x4 wq[4][4];      // W fragments of steps j .. j+3 (set = step % 4)
+  u32x4 bq[16];        // X fragments of the current step; each is refilled for the next step once consumed
+#define DG_LOAD_X(STEP, I)                                                                                   \
   {                                                                                                          \
     const int st_ = (STEP) < steps ? (STEP) : steps - 1;                                                     \
-    u32x4* dst_ = lds + ((STEP) % DG_STAGES) * DG_STAGE_U4 + (w * 2) * 64;                                   \
-    const char* xs_ = xbase + (size_t)st_ * 64;                                                              \
-    __builtin_amdgcn_global_load_lds(xs_ + xoff[0], dst_, 16, 0, 0);                                         \
-    __builtin_amdgcn_global_load_lds(xs_ + xoff[1], dst_ + 64, 16, 0, 0);                                    \
-    _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                            \
-      asm volatile("global_load_dwordx4 %0, %1, %2"                                                          \
-                   : "=v"(wq[SET][i]) : "v"(woff), "s"(wbase[i] + (size_t)st_ * 1024) : "memory");           \
+    __builtin_amdgcn_global_load_lds(xbase + (size_t)st_ * 64 + xoff[I],                                     \
+                                     lds + ((STEP) % DG_STAGES) * (DG_STAGE_BYTES / 16) + (w * 4 + (I)) * 64, 16, 0, 0); \
   }
-  // The weight loads are inline asm and the barrier is a bare s_barrier behind an explicit vmcnt wait, because
-  // the compiler's own bookkeeping would drain every load in flight (it orders nothing behind an LDS-direct
-  // load short of vmcnt(0), and so does the fence of __syncthreads).  The wait statement names the register set
-  // of the next step as read-write, which is what makes every use of those weights depend on it.
-  //
-  // One iteration = 32 MFMAs in two halves (tokens 0..63 and 64..127 of the wave's rows).  All 8 waves meet at
-  // one barrier per step, so the two waves of a SIMD run in phase and cannot hide each other's LDS latency;
-  // instead all activation fragments of step KS + 1 are read from LDS between the halves of step KS (the low
-  // half into the registers the first half has just consumed, the high half into a second set), so that their
-  // latency passes behind the 16 MFMAs of the second half.
-#define DG_ITER(KS, SET, NSET, HC, HN)                                                                       \
+#define DG_LOAD_W(STEP, SET, I)                                                                                 \
   {                                                                                                          \
-    bf16x8 a[4];                                                                                             \
-    _Pragma("unroll") for (int i = 0; i < 4; ++i) a[i] = __builtin_bit_cast(bf16x8, wq[SET][i]);             \
-    _Pragma("unroll") for (int nt = 0; nt < 4; ++nt)                                                         \
-      _Pragma("unroll") for (int mt = 0; mt < 4; ++mt)                                                       \
-        acc[nt][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[nt], blo[mt], acc[nt][mt], 0, 0, 0);         \
-    __builtin_amdgcn_sched_barrier(0);                                                                       \
-    /* step KS+1: X is in LDS for all waves, this wave's weights are in wq[NSET] */                          \
-    asm volatile("s_waitcnt vmcnt(6)\n\ts_barrier"                                                            \
-                 : "+v"(wq[NSET][0]), "+v"(wq[NSET][1]), "+v"(wq[NSET][2]), "+v"(wq[NSET][3])::"memory");    \
-    const u32x4* fb = lds + (((KS) + 1) % DG_STAGES) * DG_STAGE_U4 + (wm * 8) * 64 + lane;                   \
-    _Pragma("unroll") for (int i = 0; i < 4; ++i) blo[i] = __builtin_bit_cast(bf16x8, fb[i * 64]);           \
-    _Pragma("unroll") for (int i = 0; i < 4; ++i) bhi[HN][i] = __builtin_bit_cast(bf16x8, fb[(4 + i) * 64]); \
-    __builtin_amdgcn_sched_barrier(0);                                                                       \
-    _Pragma("unroll") for (int nt = 0; nt < 4; ++nt)                                                         \
-      _Pragma("unroll") for (int mt = 0; mt < 4; ++mt)                                                       \
-        acc[nt][4 + mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[nt], bhi[HC][mt], acc[nt][4 + mt], 0, 0, 0); \
-    __builtin_amdgcn_sched_barrier(0);                                                                       \
-    DG_ISSUE((KS) + DG_STAGES - 1, SET)                                                                      \
-    __builtin_amdgcn_sched_barrier(0);                                                                       \
+    const int st_ = (STEP) < steps ? (STEP) : steps - 1;                                                     \
+    asm volatile("global_load_dwordx4 %0, %1, %2"                                                            \
+                 : "=v"(wq[SET][I]) : "v"(woff), "s"(wbase[I] + (size_t)st_ * 1024) : "memory");             \
   }
-  DG_ISSUE(0, 0)
-  DG_ISSUE(1, 1)
-  DG_ISSUE(2, 2)
-  bf16x8 blo[4], bhi[2][4];
-  asm volatile("s_waitcnt vmcnt(12)\n\ts_barrier"
+#define DG_ISSUE(STEP)                                                                                       \
+  _Pragma("unroll") for (int i = 0; i < 4; ++i) { DG_LOAD_X(STEP, i) DG_LOAD_W(STEP, STEP, i) }
+#define DG_MFMA(ACC, A, B)                                                                                   \
+  asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(ACC) : "v"(A), "v"(B))
+  // One iteration = K step KS (KS % 4 == U, so that register sets and LDS stages are compile-time names).  At its
+  // top: this wave's loads of step KS+1 have landed (the 8 of step KS+2 may be in flight), then the barrier: X step
+  // KS+1 is in LDS for everybody, and everybody is past reading X step KS-1, whose buffer this iteration's
+  // LDS-direct loads refill.  The 16 token tiles follow; fragment mt of step KS was read 16 LDS reads ago
+  // (lgkmcnt(15)), feeds 4 MFMAs and is at once re-read for step KS+1, so that every LDS read has 60 MFMAs to
+  // arrive.
+#define DG_ITER(KS, U)                                                                                       \
+  {                                                                                                          \
+    asm volatile("s_waitcnt vmcnt(8)\n\ts_barrier"                                                            \
+                 : "+v"(wq[((U) + 1) % 4][0]), "+v"(wq[((U) + 1) % 4][1]), "+v"(wq[((U) + 1) % 4][2]),       \
+                   "+v"(wq[((U) + 1) % 4][3])::"memory");                                                    \
+    const unsigned rd_ = lds_rd + (((U) + 1) % DG_STAGES) * DG_STAGE_BYTES;                                  \
+    _Pragma("unroll") for (int mt = 0; mt < 16; ++mt) {                                                      \
+      asm volatile("s_waitcnt lgkmcnt(15)" : "+v"(bq[mt]));                                                  \
+      _Pragma("unroll") for (int nt = 0; nt < 4; ++nt) DG_MFMA(acc[nt][mt], wq[U][nt], bq[mt]);              \
+      asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(bq[mt]) : "v"(rd_), "n"(mt * 1024));               \
+      if (mt % 4 == 1) DG_LOAD_X((KS) + 3, mt / 4)                                                           \
+      if (mt % 4 == 3) DG_LOAD_W((KS) + 3, ((U) + 3) % 4, mt / 4)                                            \
+    }                                                                                                        \
+  }
+  DG_ISSUE(0)
+  DG_ISSUE(1)
+  DG_ISSUE(2)
+  asm volatile("s_waitcnt vmcnt(16)\n\ts_barrier"
                : "+v"(wq[0][0]), "+v"(wq[0][1]), "+v"(wq[0][2]), "+v"(wq[0][3])::"memory");
-  {
-    const u32x4* fb = lds + (wm * 8) * 64 + lane;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      blo[i] = __builtin_bit_cast(bf16x8, fb[i * 64]);
-      bhi[0][i] = __builtin_bit_cast(bf16x8, fb[(4 + i) * 64]);
-    }
-  }
+  for (int mt = 0; mt < 16; ++mt)
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(bq[mt]) : "v"(lds_rd), "n"(mt * 1024));
   int ks = 0;
-  for (; ks + 6 <= steps; ks += 6) {
-    DG_ITER(ks, 0, 1, 0, 1)
-    DG_ITER(ks + 1, 1, 2, 1, 0)
-    DG_ITER(ks + 2, 2, 0, 0, 1)
-    DG_ITER(ks + 3, 0, 1, 1, 0)
-    DG_ITER(ks + 4, 1, 2, 0, 1)
-    DG_ITER(ks + 5, 2, 0, 1, 0)
+  for (; ks + 4 <= steps; ks += 4) {
+    DG_ITER(ks, 0)
+    DG_ITER(ks + 1, 1)
+    DG_ITER(ks + 2, 2)
+    DG_ITER(ks + 3, 3)
   }
-  if (ks < steps) DG_ITER(ks, 0, 1, 0, 1)
-  if (ks + 1 < steps) DG_ITER(ks + 1, 1, 2, 1, 0)
-  if (ks + 2 < steps) DG_ITER(ks + 2, 2, 0, 0, 1)
-  if (ks + 3 < steps) DG_ITER(ks + 3, 0, 1, 1, 0)
-  if (ks + 4 < steps) DG_ITER(ks + 4, 1, 2, 0, 1)
+  if (ks < steps) DG_ITER(ks, 0)
+  if (ks + 1 < steps) DG_ITER(ks + 1, 1)
+  if (ks + 2 < steps) DG_ITER(ks + 2, 2)
 #undef DG_ITER
+#undef DG_MFMA
 #undef DG_ISSUE
-  // The redundant tail loads must not outlive the workgroup's LDS, and their destination registers must not be
-  // handed to anything else while they are in flight: naming every set here keeps them allocated until now.
-  asm volatile("s_waitcnt vmcnt(0)"
+#undef DG_LOAD_X
+#undef DG_LOAD_W
+  // The redundant tail loads must not outlive the workgroup's LDS, and the registers they (and the last LDS
+  // reads) target must not be handed to anything else while they are in flight: naming them here keeps them
+  // allocated until everything has landed.  The s_nops cover the distance the hardware wants between the last
+  // MFMA and a read of its accumulator.
+  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_nop 15\n\ts_nop 15"
                : "+v"(wq[0][0]), "+v"(wq[0][1]), "+v"(wq[0][2]), "+v"(wq[0][3]), "+v"(wq[1][0]), "+v"(wq[1][1]),
                  "+v"(wq[1][2]), "+v"(wq[1][3]), "+v"(wq[2][0]), "+v"(wq[2][1]), "+v"(wq[2][2]), "+v"(wq[2][3])::"memory");
+  asm volatile("" : "+v"(wq[3][0]), "+v"(wq[3][1]), "+v"(wq[3][2]), "+v"(wq[3][3]));
+  asm volatile("" : "+v"(bq[0]), "+v"(bq[1]), "+v"(bq[2]), "+v"(bq[3]), "+v"(bq[4]), "+v"(bq[5]), "+v"(bq[6]),
+               "+v"(bq[7]), "+v"(bq[8]), "+v"(bq[9]), "+v"(bq[10]), "+v"(bq[11]), "+v"(bq[12]), "+v"(bq[13]),
+               "+v"(bq[14]), "+v"(bq[15]));
 
   // acc[nt][mt][r] = Y[m0 + 16 mt + c][n0 + 16 nt + 4 kb + r]
-  const int m0 = tm * DG_BM + wm * 128, n0 = tn * DG_BN + wn * 64;
+  const int m0 = tm * DG_BM, n0 = tn * DG_BN + w * 64;
 #pragma unroll
-  for (int mt = 0; mt < 8; ++mt) {
+  for (int mt = 0; mt < 16; ++mt) {
     const int m = m0 + mt * 16 + c;
     if (m >= M) continue;
     if (EPI == DG_EPI_SWIGLU) {
