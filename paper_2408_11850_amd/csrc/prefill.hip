@@ -27,8 +27,13 @@
 #define DG_BM 256
 #define DG_BN 256
 #define DG_THREADS 256
-#define DG_STAGES 4                    // LDS ring of X steps
-#define DG_STAGE_BYTES 16384           // 16 activation blocks of 1 KiB
+// LDS ring of X: a stage holds two K steps (64 k) of the 256 tokens.  Per 16-token tile two 1 KiB blocks (rows
+// 0-7 and rows 8-15, each [8 k-chunks of 16 bytes][8 rows]), the second 128 bytes further than it needs to be,
+// which puts the two halves of a fragment read on complementary LDS banks.
+#define DG_STAGES 3
+#define DG_TILE_BYTES 2304             // 1024 + 128 (skew) + 1024 + 128
+#define DG_HALF_BYTES 1152
+#define DG_STAGE_BYTES (16 * DG_TILE_BYTES)
 
 enum { DG_EPI_STORE = 0, DG_EPI_RESID = 1, DG_EPI_SWIGLU = 2 };
 
@@ -41,7 +46,7 @@ __global__ __launch_bounds__(DG_THREADS, 1) void dense_gemm_kernel(const bf16* _
                                                                    const u32x4* __restrict__ Wp,
                                                                    float* __restrict__ Y, bf16* __restrict__ Z, int M,
                                                                    int N, int K, int NT, int steps, int TM, int cx) {
-  __shared__ u32x4 lds[DG_STAGES * DG_STAGE_BYTES / 16];
+  extern __shared__ u32x4 lds[];          // DG_STAGES * DG_STAGE_BYTES
   const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;   // w: wave-uniform
   // Workgroups are dealt to the 8 XCDs round-robin; XCD x owns tile columns [x cx, (x+1) cx) and walks them in
   // groups of 4 columns x all row tiles, so the 32 workgroups an XCD runs together share 8 x 4 operand strips
@@ -67,14 +72,18 @@ __global__ __launch_bounds__(DG_THREADS, 1) void dense_gemm_kernel(const bf16* _
   }
   const unsigned woff = lane * 16;
   const char* xbase = reinterpret_cast<const char*>(X);
-  unsigned xoff[4];                       // the 4 activation blocks this wave brings into every LDS stage
+  // X moves global -> LDS in whole 128-byte lines: one LDS-direct load covers 8 token rows x 64 k (lane = k-chunk
+  // * 8 + row), so that L2 sees every line of X once (a 16-row x 32-k load would ask for each line twice, half
+  // used).  Per stage the wave issues 8 of them: token tiles 4w .. 4w+3, rows 0-7 and 8-15 of each.
+  unsigned xoff[8];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    int m = tm * DG_BM + (w * 4 + i) * 16 + c;
+  for (int i = 0; i < 8; ++i) {
+    int m = tm * DG_BM + (w * 4 + i / 2) * 16 + (i & 1) * 8 + (lane & 7);
     if (m > M - 1) m = M - 1;
-    xoff[i] = (unsigned)m * (unsigned)K * 2u + kb * 16;     // < 2^32: checked by the launcher
+    xoff[i] = (unsigned)m * (unsigned)K * 2u + (lane >> 3) * 16;     // < 2^32: checked by the launcher
   }
-  const unsigned lds_rd = (unsigned)(size_t)(dg_lds_u32x4*)lds + lane * 16;   // LDS byte address of this lane's slot
+  // fragment (tile mt, step half h) of lane (c, kb): tile mt, block c / 8, chunk 4 h + kb, row c % 8
+  const unsigned lds_rd = (unsigned)(size_t)(dg_lds_u32x4*)lds + (c >> 3) * DG_HALF_BYTES + kb * 128 + (c & 7) * 16;
 
   f32x4 acc[4][16];
 #pragma unroll
@@ -82,58 +91,70 @@ __global__ __launch_bounds__(DG_THREADS, 1) void dense_gemm_kernel(const bf16* _
 #pragma unroll
     for (int b = 0; b < 16; ++b) acc[a][b] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  // Load schedule per wave: iteration j issues the 4 LDS-direct loads of X step j+3 and the 4 register loads of
-  // W step j+3, alternating, one after every second token tile, i.e. 8 MFMAs apart: the address unit takes
-  // about 30 cycles per 1 KiB wave load, and a wave that issues loads back to back sits in the issue stage
-  // (issuing no MFMAs) until the unit has taken them all.  Vector-memory operations complete in order.  Steps past
-  // the end reload the last step (into a free buffer / a dead register set), which keeps the count of
-  // outstanding loads uniform so that one vmcnt threshold serves every iteration.
+  // Load schedule per wave: iteration j issues 4 of the 8 LDS-direct loads of X stage j/2 + 2 (K steps 2(j/2)+4
+  // and +5) and the 4 register loads of W step j+3, alternating, one after every second token tile, i.e. 8 MFMAs
+  // apart: the address unit takes about 30 cycles per 1 KiB wave load, and a wave that issues loads back to back
+  // sits in the issue stage (issuing no MFMAs) until the unit has taken them all.  Vector-memory operations
+  // complete in order.  Steps past the end reload the last step (into a free buffer / a dead register set),
+  // which keeps the count of outstanding loads uniform so that one vmcnt threshold serves every iteration.
   u32x4 wq[4][4];      // W fragments of steps j .. j+3 (set = step % 4)
   u32x4 bq[16];        // X fragments of the current step; each is refilled for the next step once consumed
-#define DG_LOAD_X(STEP, I)                                                                                   \
+  const unsigned xfix = (lane >> 5) * 64;   // lanes of the second K step of a stage: fall back to the first one
+#define DG_LOAD_X(PG, J)   /* instruction J (0..7) of X stage PG: token tile 4w + J/2, rows 8 (J%2) .. + 7 */    \
   {                                                                                                          \
-    const int st_ = (STEP) < steps ? (STEP) : steps - 1;                                                     \
-    __builtin_amdgcn_global_load_lds(xbase + (size_t)st_ * 64 + xoff[I],                                     \
-                                     lds + ((STEP) % DG_STAGES) * (DG_STAGE_BYTES / 16) + (w * 4 + (I)) * 64, 16, 0, 0); \
+    const int st_ = 2 * (PG) < steps ? 2 * (PG) : (steps - 1) & ~1;                                          \
+    const unsigned fix_ = st_ + 1 < steps ? 0u : xfix;   /* odd K-step count: never read past the row's end */ \
+    __builtin_amdgcn_global_load_lds(                                                                        \
+        xbase + (size_t)st_ * 64 + (xoff[J] - fix_),                                                         \
+        lds + (((PG) % DG_STAGES) * DG_STAGE_BYTES + (w * 4 + (J) / 2) * DG_TILE_BYTES + ((J) & 1) * DG_HALF_BYTES) / 16, \
+        16, 0, 0);                                                                                           \
   }
-#define DG_LOAD_W(STEP, SET, I)                                                                                 \
+#define DG_LOAD_W(STEP, SET, I)                                                                              \
   {                                                                                                          \
     const int st_ = (STEP) < steps ? (STEP) : steps - 1;                                                     \
     asm volatile("global_load_dwordx4 %0, %1, %2"                                                            \
                  : "=v"(wq[SET][I]) : "v"(woff), "s"(wbase[I] + (size_t)st_ * 1024) : "memory");             \
   }
-#define DG_ISSUE(STEP)                                                                                       \
-  _Pragma("unroll") for (int i = 0; i < 4; ++i) { DG_LOAD_X(STEP, i) DG_LOAD_W(STEP, STEP, i) }
 #define DG_MFMA(ACC, A, B)                                                                                   \
   asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(ACC) : "v"(A), "v"(B))
-  // One iteration = K step KS (KS % 4 == U, so that register sets and LDS stages are compile-time names).  At its
-  // top: this wave's loads of step KS+1 have landed (the 8 of step KS+2 may be in flight), then the barrier: X step
-  // KS+1 is in LDS for everybody, and everybody is past reading X step KS-1, whose buffer this iteration's
-  // LDS-direct loads refill.  The 16 token tiles follow; fragment mt of step KS was read 16 LDS reads ago
-  // (lgkmcnt(15)), feeds 4 MFMAs and is at once re-read for step KS+1, so that every LDS read has 60 MFMAs to
-  // arrive.
+  // One iteration = K step KS (KS % 4 == U, so that the register sets are compile-time names).  At its top: this
+  // wave's loads issued up to iteration KS-2 have landed (the 8 of iteration KS-1 may be in flight), i.e. W step
+  // KS+1 and X step KS+1's stage, then the barrier: that stage is in LDS for everybody, and everybody is past
+  // reading the stage this iteration's LDS-direct loads refill.  The 16 token tiles follow; fragment mt of step
+  // KS was read 16 LDS reads ago (lgkmcnt(15)), feeds 4 MFMAs and is at once re-read for step KS+1, so that every
+  // LDS read has 60 MFMAs to arrive.
 #define DG_ITER(KS, U)                                                                                       \
   {                                                                                                          \
     asm volatile("s_waitcnt vmcnt(8)\n\ts_barrier"                                                            \
                  : "+v"(wq[((U) + 1) % 4][0]), "+v"(wq[((U) + 1) % 4][1]), "+v"(wq[((U) + 1) % 4][2]),       \
                    "+v"(wq[((U) + 1) % 4][3])::"memory");                                                    \
-    const unsigned rd_ = lds_rd + (((U) + 1) % DG_STAGES) * DG_STAGE_BYTES;                                  \
+    const unsigned rd_ = lds_rd + ((((KS) + 1) >> 1) % DG_STAGES) * DG_STAGE_BYTES + (((KS) + 1) & 1) * 512;  \
     _Pragma("unroll") for (int mt = 0; mt < 16; ++mt) {                                                      \
       asm volatile("s_waitcnt lgkmcnt(15)" : "+v"(bq[mt]));                                                  \
       _Pragma("unroll") for (int nt = 0; nt < 4; ++nt) DG_MFMA(acc[nt][mt], wq[U][nt], bq[mt]);              \
-      asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(bq[mt]) : "v"(rd_), "n"(mt * 1024));               \
-      if (mt % 4 == 1) DG_LOAD_X((KS) + 3, mt / 4)                                                           \
+      asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(bq[mt]) : "v"(rd_), "n"(mt * DG_TILE_BYTES));      \
+      if (mt % 4 == 1) DG_LOAD_X((KS) / 2 + 2, ((U) & 1) * 4 + mt / 4)                                       \
       if (mt % 4 == 3) DG_LOAD_W((KS) + 3, ((U) + 3) % 4, mt / 4)                                            \
     }                                                                                                        \
   }
-  DG_ISSUE(0)
-  DG_ISSUE(1)
-  DG_ISSUE(2)
-  asm volatile("s_waitcnt vmcnt(16)\n\ts_barrier"
-               : "+v"(wq[0][0]), "+v"(wq[0][1]), "+v"(wq[0][2]), "+v"(wq[0][3])::"memory");
+  // prologue: X stages 0 and 1 (K steps 0..3) and W steps 0..2, all landed before the first iteration
+#pragma unroll
+  for (int j8 = 0; j8 < 8; ++j8) {
+    DG_LOAD_X(0, j8)
+    DG_LOAD_X(1, j8)
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    DG_LOAD_W(0, 0, i)
+    DG_LOAD_W(1, 1, i)
+    DG_LOAD_W(2, 2, i)
+  }
+  asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier"
+               : "+v"(wq[0][0]), "+v"(wq[0][1]), "+v"(wq[0][2]), "+v"(wq[0][3]), "+v"(wq[1][0]), "+v"(wq[1][1]),
+                 "+v"(wq[1][2]), "+v"(wq[1][3]), "+v"(wq[2][0]), "+v"(wq[2][1]), "+v"(wq[2][2]), "+v"(wq[2][3])::"memory");
 #pragma unroll
   for (int mt = 0; mt < 16; ++mt)
-    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(bq[mt]) : "v"(lds_rd), "n"(mt * 1024));
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(bq[mt]) : "v"(lds_rd), "n"(mt * DG_TILE_BYTES));
   int ks = 0;
   for (; ks + 4 <= steps; ks += 4) {
     DG_ITER(ks, 0)
@@ -146,7 +167,6 @@ __global__ __launch_bounds__(DG_THREADS, 1) void dense_gemm_kernel(const bf16* _
   if (ks + 2 < steps) DG_ITER(ks + 2, 2)
 #undef DG_ITER
 #undef DG_MFMA
-#undef DG_ISSUE
 #undef DG_LOAD_X
 #undef DG_LOAD_W
   // The redundant tail loads must not outlive the workgroup's LDS, and the registers they (and the last LDS
@@ -201,12 +221,23 @@ hipError_t launch_dense_gemm(const bf16* x, const void* wp, int M, int N, int K,
   const int cx = (TN + 7) / 8;
   const int groups = (cx + 3) / 4;
   dim3 grid(8 * groups * TM * 4), block(DG_THREADS);
+  static bool attr_set = false;
+  const size_t lds_bytes = (size_t)DG_STAGES * DG_STAGE_BYTES;   // 108 KiB: above the default dynamic-LDS limit
+  if (!attr_set) {
+    const void* fns[3] = {(const void*)dense_gemm_kernel<DG_EPI_STORE>, (const void*)dense_gemm_kernel<DG_EPI_RESID>,
+                          (const void*)dense_gemm_kernel<DG_EPI_SWIGLU>};
+    for (const void* f : fns) {
+      hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+      if (e != hipSuccess) return e;
+    }
+    attr_set = true;
+  }
   if (epi == DG_EPI_STORE)
-    dense_gemm_kernel<DG_EPI_STORE><<<grid, block, 0, st>>>(x, (const u32x4*)wp, y, z, M, N, K, NT, steps, TM, cx);
+    dense_gemm_kernel<DG_EPI_STORE><<<grid, block, lds_bytes, st>>>(x, (const u32x4*)wp, y, z, M, N, K, NT, steps, TM, cx);
   else if (epi == DG_EPI_RESID)
-    dense_gemm_kernel<DG_EPI_RESID><<<grid, block, 0, st>>>(x, (const u32x4*)wp, y, z, M, N, K, NT, steps, TM, cx);
+    dense_gemm_kernel<DG_EPI_RESID><<<grid, block, lds_bytes, st>>>(x, (const u32x4*)wp, y, z, M, N, K, NT, steps, TM, cx);
   else
-    dense_gemm_kernel<DG_EPI_SWIGLU><<<grid, block, 0, st>>>(x, (const u32x4*)wp, y, z, M, N, K, NT, steps, TM, cx);
+    dense_gemm_kernel<DG_EPI_SWIGLU><<<grid, block, lds_bytes, st>>>(x, (const u32x4*)wp, y, z, M, N, K, NT, steps, TM, cx);
   return hipGetLastError();
 }
 
