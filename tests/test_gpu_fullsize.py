@@ -5,7 +5,8 @@ The oracle cannot hold the full-depth pair, so the check is split the way the sc
     every logit row of the verify forward against the oracle;
   * the full-depth pair in the launch configuration the benchmark times (4096-token prompt, window 7, two streams):
     properties that hold at any size - a multi-token verify equals sequential single-token forwards, rollback then
-    re-verify is bit-exact, greedy PEARL = greedy SD = greedy autoregressive decoding, overlapped = serialised.
+    re-verify is bit-exact, greedy PEARL = greedy SD = greedy autoregressive decoding, overlapped = serialised,
+    and the matrix-core prompt pass leaves the same cache as verify-sized prompt forwards.
 """
 import numpy as np
 import pytest
@@ -23,10 +24,13 @@ def _rel_err(got, ref):
     return float((np.abs(got - ref).max(axis=-1) / rng).max())
 
 
+@pytest.mark.parametrize("prefill_mode", [1, 0], ids=["dense_prefill", "chunked_prefill"])
 @pytest.mark.parametrize("name", ["70b_7b", "33b_1b", "7b_1b", "small"])
-def test_full_width_truncated_pair_matches_oracle(name):
+def test_full_width_truncated_pair_matches_oracle(name, prefill_mode):
     """Every workload pair at its real widths (depth cut to 2 target layers and 1 draft layer so that the fp32
-    oracle can hold it): GQA 64/8 and 32/4, MHA with 56 and 16 heads, head_dim 64 and 128, vocab 32000 and 32256."""
+    oracle can hold it): GQA 64/8 and 32/4, MHA with 56 and 16 heads, head_dim 64 and 128, vocab 32000 and 32256.
+    The prompt goes in through the matrix-core path or as 32-token verify forwards; either way every later logit
+    row must match the oracle."""
     import paper_2408_11850_amd as amd
     from paper_2408_11850_amd import harness
     cfg = synth.config(name, depth=2, draft_depth=1)
@@ -40,6 +44,7 @@ def test_full_width_truncated_pair_matches_oracle(name):
     del tw, dw
     cfg.n_prompt, cfg.n_generate = 150, 64
     ctx = harness.make_context(cfg, target, draft, 8)
+    ctx.set_option(amd.SPEC_OPT_PREFILL, prefill_mode)
     prompt = synth.prompt_tokens(cfg.n_prompt, cfg.target.vocab, 7).tolist()
     extra = synth.prompt_tokens(16, cfg.target.vocab, 8).tolist()
     ctx.prefill(prompt)
@@ -109,6 +114,14 @@ def test_full_depth_pair_properties_in_benchmark_configuration():
         outs[algo], st = ctx.generate(algo, gamma, n_gen, uni)
         print(f"  algo {algo}: {st['steps']:.0f} steps", flush=True)
     assert outs[amd.ALGO_AR] == outs[amd.ALGO_SD] == outs[amd.ALGO_PEARL]
+    # (3b) the two prompt paths fill equivalent caches: `multi` came after the matrix-core prompt pass (the default
+    # for this shape); the same verify after 128 verify-sized prompt forwards is another bf16 evaluation order
+    ctx.set_option(amd.SPEC_OPT_PREFILL, 0)
+    ctx.prefill(prompt)
+    chunked = ctx.verify(toks, want_logits=True)
+    err = _rel_err(multi, chunked)
+    print(f"  dense vs chunked prompt pass: {err:.2e} of the logit range", flush=True)
+    assert err < 6e-2
     ctx.close()
     # (4) sampled PEARL: overlapped streams == one stream, bit for bit
     res = []
