@@ -38,6 +38,7 @@ def parse():
     ap.add_argument("--wgs", type=int, default=-1, help="projection workgroups per CU: -1 auto, 1, 2")
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the benchmark line: tokens/s of PEARL and SD over window sizes and acceptance rates")
+    ap.add_argument("--sweep-part", default="all", help="with --sweep: all | gamma | cu (which part of the study to run)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
     ap.add_argument("--no-side", action="store_true", help="skip AR / SD / forced-acceptance side runs")
     return ap.parse_args()
@@ -144,7 +145,7 @@ def sweep(args, cfg, ctx, amd, synth, sync, n0, tp, tq, log):
 
     ar = run(amd.ALGO_AR, 1, 2, None)
     log(f"[sweep] AR: {ar[0]:.2f} tok/s, {ar[2]:.2f} ms/step; c = {tp / tq:.2f}")
-    for alpha in (None, 0.7, 0.9):
+    for alpha in (None, 0.7, 0.9) if args.sweep_part in ("all", "gamma") else ():
         for g in (2, 3, 4, 6, 8, 10, 12):
             r = {"alpha": "pair" if alpha is None else alpha, "gamma": g}
             for name, algo, wgs in (("pearl_1wg", amd.ALGO_PEARL, 1), ("pearl_2wg", amd.ALGO_PEARL, 2),
@@ -153,8 +154,32 @@ def sweep(args, cfg, ctx, amd, synth, sync, n0, tp, tq, log):
                 r[name] = {"tokens_per_s": round(tps, 2), "tokens_per_step": round(tpstep, 3), "step_ms": round(ms, 2)}
             rows.append(r)
             log(f"[sweep] {json.dumps(r)}")
+    # CU partition between the two streams (the paper's resource-competition setting, Appendix on RC): the target
+    # stream gets the first T compute units, the draft stream the rest; decisions forced to Bernoulli(0.9) so that
+    # every point sees the same mix of pre- and post-verify steps
+    from paper_2408_11850_amd import harness
+    prompt = synth.prompt_tokens(cfg.n_prompt, cfg.target.vocab, cfg.seed_prompt).tolist()
+    g = args.gamma or 7
+    split_rows = []
+    for t_cus in (None, 256, 224, 192, 160, 128, 96, None) if args.sweep_part in ("all", "cu") else ():
+        c2 = harness.make_context(cfg, ctx.target, ctx.draft, 16, extra_seq=64, target_cus=t_cus)
+        c2.prefill(prompt)
+        r = {"target_cus": t_cus or "all (plain streams)", "draft_cus": "all" if not t_cus or t_cus >= 256 else 256 - t_cus}
+        for wgs in (1, 2):
+            c2.set_option(amd.SPEC_OPT_GEMM_WGS_PER_CU, wgs)
+            c2.rewind(n0)
+            u = synth.make_uniforms(steps + 8, g, cfg.seed_uniform)
+            fb = (synth.uniform_array((steps + 8) * (g + 1), 5, 7).view(steps + 8, g + 1).numpy() < 0.9)
+            c2.generate(amd.ALGO_PEARL, g, 1 << 20, u, force_bits=fb, max_steps=6)   # captures every graph variant
+            sync(); t0 = time.perf_counter()
+            _, s2 = c2.generate(amd.ALGO_PEARL, g, 1 << 20, u, force_bits=fb, max_steps=steps)
+            sync(); dt = time.perf_counter() - t0
+            r[f"pearl_{wgs}wg"] = {"tokens_per_s": round(s2["committed"] / dt, 2), "step_ms": round(dt / s2["steps"] * 1e3, 2)}
+        c2.close()
+        split_rows.append(r)
+        log(f"[sweep] cu split {json.dumps(r)}")
     print(json.dumps({"workload": cfg.name, "n_prompt": n0, "steps_per_point": steps, "c": tp / tq,
-                      "ar_tokens_per_s": ar[0], "rows": rows}))
+                      "ar_tokens_per_s": ar[0], "rows": rows, "cu_split_gamma": g, "cu_split": split_rows}))
 
 
 def main():

@@ -84,7 +84,11 @@ typedef struct {
   float temperature;  /* 0 = greedy (distributions become one-hot at the arg-max)           */
   float logit_scale;  /* logits are multiplied by this before the softmax                   */
   void* stream_target;/* hipStream_t, borrowed                                              */
-  void* stream_draft; /* hipStream_t, borrowed; may equal stream_target (serialised)        */
+  void* stream_draft; /* hipStream_t, borrowed; may equal stream_target (serialised).  For the two
+                         passes to overlap the streams must sit on different hardware queues: plain
+                         streams are dealt round-robin to a few shared queues and may end up on the
+                         same one; a stream from hipExtStreamCreateWithCUMask (a mask of all compute
+                         units will do) owns a queue.  Default priority only.               */
 } spec_config;
 
 /* ---- the decoding path --------------------------------------------------------------- */

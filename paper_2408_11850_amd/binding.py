@@ -118,8 +118,11 @@ class SpecContext:
     """One target/draft pair with its caches: the calls of include/spec.h as methods."""
 
     def __init__(self, target: PackedModel, draft: PackedModel, gamma_max: int, max_seq: int,
-                 temperature: float = 1.0, logit_scale: float = 1.0, stream_target=None, stream_draft=None):
+                 temperature: float = 1.0, logit_scale: float = 1.0, stream_target=None, stream_draft=None,
+                 on_close=None):
+        """on_close: called after the context is freed (e.g. to destroy streams made for it)."""
         self.lib = load_library()
+        self._on_close = on_close
         self.target, self.draft = target, draft
         self.stream_target = stream_target or torch.cuda.Stream()
         self.stream_draft = stream_draft or torch.cuda.Stream()
@@ -138,6 +141,9 @@ class SpecContext:
         if getattr(self, "_ctx", None):
             self.lib.spec_free(self._ctx)
             self._ctx = None
+            if self._on_close:
+                self._on_close()
+                self._on_close = None
 
     def __del__(self):
         try:

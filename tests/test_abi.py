@@ -45,6 +45,16 @@ def test_argument_validation_without_a_gpu(amd):
     assert lib.spec_verify(None, None, 1, None) == amd.SPEC_E_INVAL
     assert lib.spec_rollback_kv(None, 0, 0) == amd.SPEC_E_INVAL
     assert lib.spec_pack_weight(None, None, 16, 8, 0, 1, None) == amd.SPEC_E_INVAL
+    # the prompt-sized projection validates before it launches: null operands, bad epilogue, K not a multiple of 32,
+    # N not a multiple of 16 (32 for the gate/up epilogue), missing output
+    p = C.c_void_p(256)
+    assert lib.spec_dense_gemm(p, None, None, p, 4, 64, 64, 0, None) == amd.SPEC_E_INVAL
+    assert lib.spec_dense_gemm(p, None, p, p, 4, 64, 64, 3, None) == amd.SPEC_E_INVAL
+    assert lib.spec_dense_gemm(p, None, p, p, 4, 64, 48, 0, None) == amd.SPEC_E_INVAL
+    assert lib.spec_dense_gemm(p, None, p, p, 4, 40, 64, 0, None) == amd.SPEC_E_INVAL
+    assert lib.spec_dense_gemm(None, p, p, p, 4, 48, 64, 2, None) == amd.SPEC_E_INVAL
+    assert lib.spec_dense_gemm(None, None, p, p, 4, 64, 64, 1, None) == amd.SPEC_E_INVAL
+    assert lib.spec_set_option(None, amd.SPEC_OPT_PREFILL, 1) == amd.SPEC_E_INVAL
     cfg = amd.Config(4, 128, 64, 1.0, 1.0, None, None)
     bad = amd.ModelDesc(2, 256, 4, 3, 64, 688, 1024, 10000.0, 1e-5)     # heads not a multiple of kv heads
     w = amd.Weights()
