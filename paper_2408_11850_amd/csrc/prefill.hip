@@ -14,8 +14,9 @@
 //   * every weight fragment is used by exactly one wave, which loads it straight from global memory into
 //     registers three K steps ahead (no LDS traffic, no duplicate loads), through a ring of four register sets;
 //   * X is needed by all four waves and goes global -> LDS once per workgroup with the LDS-direct loads of
-//     gfx950 (global_load_lds_dwordx4: lane l lands at base + 16 l, i.e. already in operand order); a wave
-//     reads each of its 16 fragments back with one conflict-free ds_read_b128.
+//     gfx950 (global_load_lds_dwordx4: lane l lands at base + 16 l), whole 128-byte lines at a time (8 token
+//     rows x 64 k per instruction, so L2 is asked for every line once); a wave reads each of its 16 fragments
+//     back with one ds_read_b128 (free of bank conflicts).
 // Per 32-wide K step that is 32 KiB from L2 and 80 KiB through LDS for 64 MFMAs per wave (1024 MFMA cycles).
 //
 // The inner loop is inline asm with hand-placed waits.  The compiler cannot be trusted with it: it drains every
@@ -28,11 +29,12 @@
 #define DG_BN 256
 #define DG_THREADS 256
 // LDS ring of X: a stage holds two K steps (64 k) of the 256 tokens.  Per 16-token tile two 1 KiB blocks (rows
-// 0-7 and rows 8-15, each [8 k-chunks of 16 bytes][8 rows]), the second 128 bytes further than it needs to be,
-// which puts the two halves of a fragment read on complementary LDS banks.
+// 0-7 and rows 8-15, each [8 k-chunks of 16 bytes][8 rows]).  A fragment read takes 128 contiguous bytes from
+// each block per 16 lanes; SQ_LDS_BANK_CONFLICT is 0 for this layout (and for the blocks 1280 bytes apart), while
+// blocks 1088 or 1152 bytes apart double the LDS cycles.
 #define DG_STAGES 3
-#define DG_TILE_BYTES 2304             // 1024 + 128 (skew) + 1024 + 128
-#define DG_HALF_BYTES 1152
+#define DG_HALF_BYTES 1024
+#define DG_TILE_BYTES (2 * DG_HALF_BYTES)
 #define DG_STAGE_BYTES (16 * DG_TILE_BYTES)
 
 enum { DG_EPI_STORE = 0, DG_EPI_RESID = 1, DG_EPI_SWIGLU = 2 };
@@ -222,7 +224,7 @@ hipError_t launch_dense_gemm(const bf16* x, const void* wp, int M, int N, int K,
   const int groups = (cx + 3) / 4;
   dim3 grid(8 * groups * TM * 4), block(DG_THREADS);
   static bool attr_set = false;
-  const size_t lds_bytes = (size_t)DG_STAGES * DG_STAGE_BYTES;   // 108 KiB: above the default dynamic-LDS limit
+  const size_t lds_bytes = (size_t)DG_STAGES * DG_STAGE_BYTES;   // 96 KiB: above the default dynamic-LDS limit
   if (!attr_set) {
     const void* fns[3] = {(const void*)dense_gemm_kernel<DG_EPI_STORE>, (const void*)dense_gemm_kernel<DG_EPI_RESID>,
                           (const void*)dense_gemm_kernel<DG_EPI_SWIGLU>};
