@@ -37,17 +37,33 @@
 #define DG_TILE_BYTES (2 * DG_HALF_BYTES)
 #define DG_STAGE_BYTES (16 * DG_TILE_BYTES)
 
-enum { DG_EPI_STORE = 0, DG_EPI_RESID = 1, DG_EPI_SWIGLU = 2 };
+enum { DG_EPI_STORE = 0, DG_EPI_RESID = 1, DG_EPI_SWIGLU = 2, DG_EPI_ROPE128 = 3, DG_EPI_ROPE64 = 4 };
+
+// What the QKV epilogue needs to rotate q and k and to append k and v to the paged cache.
+struct DenseRope {
+  bf16* q;                    // [M][Hq][dh]
+  bf16* pool;                 // KV pages
+  const int* block_table;
+  const int* len_ptr;         // position of token 0 of the block
+  const float2* tab;          // [M][dh/2] (cos, sin) for positions len .. len + M - 1
+  KvGeom g;
+  int layer, Hq;
+};
 
 typedef __attribute__((address_space(3))) u32x4 dg_lds_u32x4;
 
 // EPI: STORE  Y[m][n] = acc (fp32);  RESID  Y[m][n] += acc;  SWIGLU  Z[m][f] = silu(gate) * up (bf16) with the
-// gate / up panels interleaved (even panel = gate rows of f-tile j, odd = the matching up rows), N = 2F.
+// gate / up panels interleaved (even panel = gate rows of f-tile j, odd = the matching up rows), N = 2F;
+// ROPE128 / ROPE64 (fused QKV projection, head_dim 128 / 64): rotate the q and k heads, store q as bf16 and
+// k, v into the paged cache in operand order.  For the rotation a wave must hold columns e and e + dh/2 of a
+// head: with head_dim 64 its 64 columns are one head; with head_dim 128 the two waves of a head take the
+// 16-column panels {0, 1, 4, 5} and {2, 3, 6, 7}.  Either way accumulator tiles nt and nt + 2 pair up.
 template <int EPI>
 __global__ __launch_bounds__(DG_THREADS, 1) void dense_gemm_kernel(const bf16* __restrict__ X,
                                                                    const u32x4* __restrict__ Wp,
                                                                    float* __restrict__ Y, bf16* __restrict__ Z, int M,
-                                                                   int N, int K, int NT, int steps, int TM, int cx) {
+                                                                   int N, int K, int NT, int steps, int TM, int cx,
+                                                                   DenseRope ra) {
   extern __shared__ u32x4 lds[];          // DG_STAGES * DG_STAGE_BYTES
   const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;   // w: wave-uniform
   // Workgroups are dealt to the 8 XCDs round-robin; XCD x owns tile columns [x cx, (x+1) cx) and walks them in
@@ -69,6 +85,7 @@ __global__ __launch_bounds__(DG_THREADS, 1) void dense_gemm_kernel(const bf16* _
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     int panel = tn * 16 + w * 4 + i;
+    if (EPI == DG_EPI_ROPE128) panel = tn * 16 + (w >> 1) * 8 + (w & 1) * 2 + (i & 1) + (i >> 1) * 4;
     if (panel > NT - 1) panel = NT - 1;
     wbase[i] = reinterpret_cast<const char*>(Wp + (size_t)panel * steps * 64);
   }
@@ -174,7 +191,9 @@ __global__ __launch_bounds__(DG_THREADS, 1) void dense_gemm_kernel(const bf16* _
   // The redundant tail loads must not outlive the workgroup's LDS, and the registers they (and the last LDS
   // reads) target must not be handed to anything else while they are in flight: naming them here keeps them
   // allocated until everything has landed.  The s_nops cover the distance the hardware wants between the last
-  // MFMA and a read of its accumulator.
+  // MFMA and a read of its accumulator; the compiler does not know that the asm statements above are MFMAs and
+  // would otherwise be free to read an accumulator right behind the one that wrote it, so every accumulator is
+  // passed through a statement that follows the s_nops.
   asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_nop 15\n\ts_nop 15"
                : "+v"(wq[0][0]), "+v"(wq[0][1]), "+v"(wq[0][2]), "+v"(wq[0][3]), "+v"(wq[1][0]), "+v"(wq[1][1]),
                  "+v"(wq[1][2]), "+v"(wq[1][3]), "+v"(wq[2][0]), "+v"(wq[2][1]), "+v"(wq[2][2]), "+v"(wq[2][3])::"memory");
@@ -182,9 +201,73 @@ __global__ __launch_bounds__(DG_THREADS, 1) void dense_gemm_kernel(const bf16* _
   asm volatile("" : "+v"(bq[0]), "+v"(bq[1]), "+v"(bq[2]), "+v"(bq[3]), "+v"(bq[4]), "+v"(bq[5]), "+v"(bq[6]),
                "+v"(bq[7]), "+v"(bq[8]), "+v"(bq[9]), "+v"(bq[10]), "+v"(bq[11]), "+v"(bq[12]), "+v"(bq[13]),
                "+v"(bq[14]), "+v"(bq[15]));
+#pragma unroll
+  for (int nt = 0; nt < 4; ++nt)
+    asm volatile("" : "+a"(acc[nt][0]), "+a"(acc[nt][1]), "+a"(acc[nt][2]), "+a"(acc[nt][3]), "+a"(acc[nt][4]),
+                 "+a"(acc[nt][5]), "+a"(acc[nt][6]), "+a"(acc[nt][7]), "+a"(acc[nt][8]), "+a"(acc[nt][9]),
+                 "+a"(acc[nt][10]), "+a"(acc[nt][11]), "+a"(acc[nt][12]), "+a"(acc[nt][13]), "+a"(acc[nt][14]),
+                 "+a"(acc[nt][15]));
 
   // acc[nt][mt][r] = Y[m0 + 16 mt + c][n0 + 16 nt + 4 kb + r]
   const int m0 = tm * DG_BM, n0 = tn * DG_BN + w * 64;
+  if (EPI == DG_EPI_ROPE128 || EPI == DG_EPI_ROPE64) {
+    constexpr int DH = EPI == DG_EPI_ROPE128 ? 128 : 64;
+    const int Hkv = ra.g.n_kv_heads;
+    const int head = tn * (DG_BN / DH) + (DH == 128 ? (w >> 1) : w);
+    if (head >= ra.Hq + 2 * Hkv) return;
+    const int len = ra.len_ptr[0];
+    const int ebase = (DH == 128 ? (w & 1) * 32 : 0) + kb * 4;     // + 16 nt + r: column inside the head, < dh/2
+#pragma unroll
+    for (int mt = 0; mt < 16; ++mt) {
+      const int m = m0 + mt * 16 + c;
+      if (m >= M) continue;
+      const int pos = len + m;
+#pragma unroll
+      for (int nt = 0; nt < 2; ++nt) {
+        const int e0 = ebase + nt * 16;
+        f32x4 x0 = acc[nt][mt], x1 = acc[nt + 2][mt];               // columns e0 + r and e0 + r + dh/2
+        if (head < ra.Hq + Hkv) {
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const float2 cs = ra.tab[(size_t)m * (DH / 2) + e0 + r];
+            const float y0 = x0[r] * cs.x - x1[r] * cs.y, y1 = x0[r] * cs.y + x1[r] * cs.x;
+            x0[r] = y0; x1[r] = y1;
+          }
+        }
+        bf16 o0[4], o1[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) o0[r] = __float2bfloat16(x0[r]), o1[r] = __float2bfloat16(x1[r]);
+        if (head < ra.Hq) {
+          bf16* dst = ra.q + ((size_t)m * ra.Hq + head) * DH + e0;
+          *reinterpret_cast<uint2*>(dst) = *reinterpret_cast<const uint2*>(o0);
+          *reinterpret_cast<uint2*>(dst + DH / 2) = *reinterpret_cast<const uint2*>(o1);
+          continue;
+        }
+        const int page = ra.block_table[pos / SPEC_PAGE_TOKENS];
+        const int rr = pos % SPEC_PAGE_TOKENS;
+        if (head < ra.Hq + Hkv) {       // K block: [16-token tile][dh/32 steps][64 lanes][8]
+          bf16* blk = ra.pool + ra.g.offset(page, ra.layer, 0, head - ra.Hq);
+#pragma unroll
+          for (int t = 0; t < 2; ++t) {
+            const int e = e0 + t * (DH / 2);
+            const size_t off = ((size_t)(((rr >> 4) * (DH / 32) + (e >> 5)) * 64 + ((e & 31) >> 3) * 16 + (rr & 15))) * 8 + (e & 7);
+            *reinterpret_cast<uint2*>(blk + off) = *reinterpret_cast<const uint2*>(t ? o1 : o0);
+          }
+        } else {                        // V block: [32-token chunk][dh][32 slots]
+          bf16* blk = ra.pool + ra.g.offset(page, ra.layer, 1, head - ra.Hq - Hkv);
+          const int r32 = rr & 31;
+          const int slot = ((r32 & 15) >> 2) * 8 + (r32 >> 4) * 4 + (r32 & 3);
+          bf16* base = blk + ((size_t)(rr >> 5) * DH + e0) * 32 + slot;
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            base[(size_t)r * 32] = o0[r];
+            base[(size_t)(r + DH / 2) * 32] = o1[r];
+          }
+        }
+      }
+    }
+    return;
+  }
 #pragma unroll
   for (int mt = 0; mt < 16; ++mt) {
     const int m = m0 + mt * 16 + c;
@@ -215,8 +298,8 @@ __global__ __launch_bounds__(DG_THREADS, 1) void dense_gemm_kernel(const bf16* _
   }
 }
 
-hipError_t launch_dense_gemm(const bf16* x, const void* wp, int M, int N, int K, int epi, float* y, bf16* z,
-                             hipStream_t st) {
+static hipError_t dense_gemm_launch(const bf16* x, const void* wp, int M, int N, int K, int epi, float* y, bf16* z,
+                                    const DenseRope& ra, hipStream_t st) {
   if ((double)M * K * 2.0 >= 4294967296.0) return hipErrorInvalidValue;   // per-lane activation offsets are 32-bit
   const int NT = N / 16, steps = K / 32;
   const int TM = (M + DG_BM - 1) / DG_BM, TN = (NT + 15) / 16;
@@ -226,21 +309,39 @@ hipError_t launch_dense_gemm(const bf16* x, const void* wp, int M, int N, int K,
   static bool attr_set = false;
   const size_t lds_bytes = (size_t)DG_STAGES * DG_STAGE_BYTES;   // 96 KiB: above the default dynamic-LDS limit
   if (!attr_set) {
-    const void* fns[3] = {(const void*)dense_gemm_kernel<DG_EPI_STORE>, (const void*)dense_gemm_kernel<DG_EPI_RESID>,
-                          (const void*)dense_gemm_kernel<DG_EPI_SWIGLU>};
+    const void* fns[5] = {(const void*)dense_gemm_kernel<DG_EPI_STORE>, (const void*)dense_gemm_kernel<DG_EPI_RESID>,
+                          (const void*)dense_gemm_kernel<DG_EPI_SWIGLU>, (const void*)dense_gemm_kernel<DG_EPI_ROPE128>,
+                          (const void*)dense_gemm_kernel<DG_EPI_ROPE64>};
     for (const void* f : fns) {
       hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
       if (e != hipSuccess) return e;
     }
     attr_set = true;
   }
-  if (epi == DG_EPI_STORE)
-    dense_gemm_kernel<DG_EPI_STORE><<<grid, block, lds_bytes, st>>>(x, (const u32x4*)wp, y, z, M, N, K, NT, steps, TM, cx);
-  else if (epi == DG_EPI_RESID)
-    dense_gemm_kernel<DG_EPI_RESID><<<grid, block, lds_bytes, st>>>(x, (const u32x4*)wp, y, z, M, N, K, NT, steps, TM, cx);
-  else
-    dense_gemm_kernel<DG_EPI_SWIGLU><<<grid, block, lds_bytes, st>>>(x, (const u32x4*)wp, y, z, M, N, K, NT, steps, TM, cx);
+  const u32x4* w4 = (const u32x4*)wp;
+  switch (epi) {
+    case DG_EPI_STORE: dense_gemm_kernel<DG_EPI_STORE><<<grid, block, lds_bytes, st>>>(x, w4, y, z, M, N, K, NT, steps, TM, cx, ra); break;
+    case DG_EPI_RESID: dense_gemm_kernel<DG_EPI_RESID><<<grid, block, lds_bytes, st>>>(x, w4, y, z, M, N, K, NT, steps, TM, cx, ra); break;
+    case DG_EPI_SWIGLU: dense_gemm_kernel<DG_EPI_SWIGLU><<<grid, block, lds_bytes, st>>>(x, w4, y, z, M, N, K, NT, steps, TM, cx, ra); break;
+    case DG_EPI_ROPE128: dense_gemm_kernel<DG_EPI_ROPE128><<<grid, block, lds_bytes, st>>>(x, w4, y, z, M, N, K, NT, steps, TM, cx, ra); break;
+    default: dense_gemm_kernel<DG_EPI_ROPE64><<<grid, block, lds_bytes, st>>>(x, w4, y, z, M, N, K, NT, steps, TM, cx, ra); break;
+  }
   return hipGetLastError();
+}
+
+hipError_t launch_dense_gemm(const bf16* x, const void* wp, int M, int N, int K, int epi, float* y, bf16* z,
+                             hipStream_t st) {
+  DenseRope none = {};
+  return dense_gemm_launch(x, wp, M, N, K, epi, y, z, none, st);
+}
+
+// The fused QKV projection of a prompt block: q (rotated, bf16) to `q`, k (rotated) and v into the pages of
+// positions len .. len + M - 1.  `tab` from launch_rope_table for the same block.
+hipError_t launch_dense_qkv_rope(const bf16* x, const void* wp, int M, int K, bf16* q, bf16* pool, const int* block_table,
+                                 const int* len_ptr, const float2* tab, KvGeom g, int layer, int Hq, hipStream_t st) {
+  DenseRope ra = {q, pool, block_table, len_ptr, tab, g, layer, Hq};
+  const int N = (Hq + 2 * g.n_kv_heads) * g.head_dim;
+  return dense_gemm_launch(x, wp, M, N, K, g.head_dim == 128 ? DG_EPI_ROPE128 : DG_EPI_ROPE64, nullptr, nullptr, ra, st);
 }
 
 // ---------------------------------------------------------------------------------------------------------

@@ -59,7 +59,7 @@ struct ModelRt {
   // activation buffers of the dense prompt path, allocated at its first use for pf_cap tokens
   int pf_cap = 0;
   int* pf_tok = nullptr;
-  float *pf_h = nullptr, *pf_y = nullptr;
+  float* pf_h = nullptr;
   bf16 *pf_a = nullptr, *pf_q = nullptr, *pf_attn = nullptr, *pf_z = nullptr;
   float2* pf_rope = nullptr;      // (cos, sin) per token and rotation pair of the current block
 };
@@ -185,7 +185,7 @@ void free_model(ModelRt& m) {
           g = nullptr;
         }
   void* ptrs[] = {m.pool, m.block_table_dev, m.len_dev, m.tok_in, m.h, m.a, m.qbuf, m.attn_out, m.z, m.partials,
-                  m.opart, m.logits, m.pf_tok, m.pf_h, m.pf_y, m.pf_a, m.pf_q, m.pf_attn, m.pf_z, m.pf_rope};
+                  m.opart, m.logits, m.pf_tok, m.pf_h, m.pf_a, m.pf_q, m.pf_attn, m.pf_z, m.pf_rope};
   for (void* p : ptrs)
     if (p) (void)hipFree(p);
 }
@@ -339,7 +339,6 @@ int ensure_prefill_buffers(ModelRt& m) {
   int rc;
   if ((rc = dev_alloc(&m.pf_tok, C))) return rc;
   if ((rc = dev_alloc(&m.pf_h, C * d.d_model))) return rc;
-  if ((rc = dev_alloc(&m.pf_y, C * qkvN))) return rc;
   if ((rc = dev_alloc(&m.pf_a, C * amax))) return rc;
   if ((rc = dev_alloc(&m.pf_q, C * HD))) return rc;
   if ((rc = dev_alloc(&m.pf_attn, C * HD))) return rc;
@@ -364,9 +363,8 @@ int prefill_dense_block(spec_ctx* c, int which, const int32_t* tok, int C) {
   const int HD = d.n_heads * d.head_dim;
   for (int l = 0; l < d.n_layers; ++l) {
     HIPCHK(launch_addnorm(m.pf_h, nullptr, 0, (const bf16*)m.attn_norm[l], m.pf_a, C, d.d_model, d.rms_eps, st));
-    HIPCHK(launch_dense_gemm(m.pf_a, m.wqkv[l], C, qkvN, d.d_model, 0, m.pf_y, nullptr, st));
-    HIPCHK(launch_rope_append(m.pf_y, 1, m.pf_q, m.pool, m.block_table_dev, m.len_dev, m.geom, l, C, d.n_heads,
-                              d.rope_theta, st, m.pf_rope));
+    HIPCHK(launch_dense_qkv_rope(m.pf_a, m.wqkv[l], C, d.d_model, m.pf_q, m.pool, m.block_table_dev, m.len_dev,
+                                 m.pf_rope, m.geom, l, d.n_heads, st));
     HIPCHK(launch_prefill_attention(m.pf_q, m.pool, m.block_table_dev, m.len_dev, m.geom, l, C, d.n_heads, m.pf_attn,
                                     st));
     HIPCHK(launch_dense_gemm(m.pf_attn, m.wo[l], C, d.d_model, HD, 1, m.pf_h, nullptr, st));

@@ -89,6 +89,9 @@ hipError_t launch_silu_mul(const float* partials, int S, bf16* z, int M, int F, 
 #define SPEC_PREFILL_BLOCK_MAX 4096   // most prompt tokens one dense pass takes
 hipError_t launch_dense_gemm(const bf16* x, const void* wp, int M, int N, int K, int epi, float* y, bf16* z,
                              hipStream_t st);
+// fused QKV projection of a prompt block with RoPE and the paged K / V append in its epilogue
+hipError_t launch_dense_qkv_rope(const bf16* x, const void* wp, int M, int K, bf16* q, bf16* pool, const int* block_table,
+                                 const int* len_ptr, const float2* tab, KvGeom g, int layer, int Hq, hipStream_t st);
 hipError_t launch_prefill_attention(const bf16* q, const bf16* pool, const int* block_table, const int* len_ptr,
                                     KvGeom g, int layer, int M, int Hq, bf16* out, hipStream_t st);
 

@@ -113,7 +113,19 @@ def test_full_depth_pair_properties_in_benchmark_configuration():
         ctx.rewind(n0)
         outs[algo], st = ctx.generate(algo, gamma, n_gen, uni)
         print(f"  algo {algo}: {st['steps']:.0f} steps", flush=True)
-    assert outs[amd.ALGO_AR] == outs[amd.ALGO_SD] == outs[amd.ALGO_PEARL]
+    # The three loops evaluate the same arg-max through different batch shapes (1, gamma + 1 and gamma rows); at 80
+    # layers those bf16 evaluation orders differ by up to a few 1e-2 of the logit range (see (1)), so the sequences
+    # may part at a near-tie of the target's top two logits - and only there.
+    for other in (amd.ALGO_SD, amd.ALGO_PEARL):
+        a, b = outs[amd.ALGO_AR], outs[other]
+        i = next((k for k in range(n_gen) if a[k] != b[k]), None)
+        if i is None:
+            continue
+        ctx.rewind(n0)
+        row = ctx.verify([prompt[-1]] + a[:i], want_logits=True)[-1]
+        gap = abs(float(row[a[i]]) - float(row[b[i]])) / float(row.max() - row.min())
+        print(f"  algo {other} parts from AR at token {i}: logit gap {gap:.2e} of the range", flush=True)
+        assert gap < 6e-2 and min(row[a[i]], row[b[i]]) >= np.sort(row)[-2] - 1e-6
     # (3b) the two prompt paths fill equivalent caches: `multi` came after the matrix-core prompt pass (the default
     # for this shape); the same verify after 128 verify-sized prompt forwards is another bf16 evaluation order
     ctx.set_option(amd.SPEC_OPT_PREFILL, 0)
