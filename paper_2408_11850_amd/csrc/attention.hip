@@ -50,65 +50,70 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const bf16* __restrict_
 #pragma unroll
   for (int dt = 0; dt < DH / 16; ++dt) o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  for (int ch = c0; ch < c1; ++ch) {
-    const int pos0 = ch << 5;
-    const int page = block_table[pos0 / SPEC_PAGE_TOKENS];
-    const int inpage = pos0 % SPEC_PAGE_TOKENS;
-    const u32x4* kblk = reinterpret_cast<const u32x4*>(pool + g.offset(page, layer, 0, kvh)) +
-                        (size_t)(inpage >> 4) * (DH / 32) * 64 + lane;
-    const bf16* vblk = pool + g.offset(page, layer, 1, kvh) + (size_t)(inpage >> 5) * DH * 32;
-    // issue all loads of the chunk first
-    u32x4 ka[2][DH / 32];
-#pragma unroll
-    for (int t = 0; t < 2; ++t)
-#pragma unroll
-      for (int j = 0; j < DH / 32; ++j) ka[t][j] = kblk[(size_t)(t * (DH / 32) + j) * 64];
-    u32x4 va[DH / 16];
-#pragma unroll
-    for (int dt = 0; dt < DH / 16; ++dt)
-      va[dt] = *reinterpret_cast<const u32x4*>(vblk + ((size_t)(dt * 16 + c) * 32 + g4 * 8));
-
-    f32x4 s[2];
-#pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      s[t] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int j = 0; j < DH / 32; ++j)
-        s[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka[t][j]), qf[j], s[t], 0, 0, 0);
-    }
-    // s[t][r] = score of position pos0 + 16 t + 4 g4 + r for query row c
-    float mx = NEG_BIG;
-#pragma unroll
-    for (int t = 0; t < 2; ++t)
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int pos = pos0 + t * 16 + g4 * 4 + r;
-        const float v = (pos <= limit) ? s[t][r] * scale : NEG_BIG;
-        s[t][r] = v;
-        mx = fmaxf(mx, v);
-      }
-    mx = fmaxf(mx, __shfl_xor(mx, 16));
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float m_new = fmaxf(m_run, mx);
-    const float corr = __expf(m_run - m_new);
-    float psum = 0.f;
-    bf16x8 pf;
-#pragma unroll
-    for (int t = 0; t < 2; ++t)
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const float p = (s[t][r] > 0.5f * NEG_BIG) ? __expf(s[t][r] - m_new) : 0.f;
-        psum += p;
-        pf[t * 4 + r] = (__bf16)p;
-      }
-    l_run = l_run * corr + psum;
-    m_run = m_new;
-#pragma unroll
-    for (int dt = 0; dt < DH / 16; ++dt) {
-      o[dt] *= corr;
-      o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, va[dt]), pf, o[dt], 0, 0, 0);
-    }
+  // K / V fragments of two chunks: while one chunk is multiplied the loads of the next are already in flight
+  // (a wave owns only a handful of chunks, so its run time is a chain of load latencies unless they overlap).
+  u32x4 ka[2][2][DH / 32], va[2][DH / 16];
+#define ATT_LOAD(B, CH)                                                                                       \
+  {                                                                                                           \
+    const int pos0_ = (CH) << 5;                                                                              \
+    const int page_ = block_table[pos0_ / SPEC_PAGE_TOKENS];                                                  \
+    const int inpage_ = pos0_ % SPEC_PAGE_TOKENS;                                                             \
+    const u32x4* kblk_ = reinterpret_cast<const u32x4*>(pool + g.offset(page_, layer, 0, kvh)) +              \
+                         (size_t)(inpage_ >> 4) * (DH / 32) * 64 + lane;                                      \
+    const bf16* vblk_ = pool + g.offset(page_, layer, 1, kvh) + (size_t)(inpage_ >> 5) * DH * 32;             \
+    _Pragma("unroll") for (int t = 0; t < 2; ++t)                                                             \
+      _Pragma("unroll") for (int j = 0; j < DH / 32; ++j) ka[B][t][j] = kblk_[(size_t)(t * (DH / 32) + j) * 64]; \
+    _Pragma("unroll") for (int dt = 0; dt < DH / 16; ++dt)                                                    \
+      va[B][dt] = *reinterpret_cast<const u32x4*>(vblk_ + ((size_t)(dt * 16 + c) * 32 + g4 * 8));             \
   }
+#define ATT_COMPUTE(B, CH)                                                                                    \
+  {                                                                                                           \
+    const int pos0 = (CH) << 5;                                                                               \
+    f32x4 s[2];                                                                                               \
+    _Pragma("unroll") for (int t = 0; t < 2; ++t) {                                                           \
+      s[t] = f32x4{0.f, 0.f, 0.f, 0.f};                                                                       \
+      _Pragma("unroll") for (int j = 0; j < DH / 32; ++j)                                                     \
+        s[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka[B][t][j]), qf[j], s[t], 0, 0, 0); \
+    }                                                                                                         \
+    /* s[t][r] = score of position pos0 + 16 t + 4 g4 + r for query row c */                                  \
+    float mx = NEG_BIG;                                                                                       \
+    _Pragma("unroll") for (int t = 0; t < 2; ++t)                                                             \
+      _Pragma("unroll") for (int r = 0; r < 4; ++r) {                                                         \
+        const int pos = pos0 + t * 16 + g4 * 4 + r;                                                           \
+        const float v = (pos <= limit) ? s[t][r] * scale : NEG_BIG;                                           \
+        s[t][r] = v;                                                                                          \
+        mx = fmaxf(mx, v);                                                                                    \
+      }                                                                                                       \
+    mx = fmaxf(mx, __shfl_xor(mx, 16));                                                                       \
+    mx = fmaxf(mx, __shfl_xor(mx, 32));                                                                       \
+    const float m_new = fmaxf(m_run, mx);                                                                     \
+    const float corr = __expf(m_run - m_new);                                                                 \
+    float psum = 0.f;                                                                                         \
+    bf16x8 pf;                                                                                                \
+    _Pragma("unroll") for (int t = 0; t < 2; ++t)                                                             \
+      _Pragma("unroll") for (int r = 0; r < 4; ++r) {                                                         \
+        const float p = (s[t][r] > 0.5f * NEG_BIG) ? __expf(s[t][r] - m_new) : 0.f;                           \
+        psum += p;                                                                                            \
+        pf[t * 4 + r] = (__bf16)p;                                                                            \
+      }                                                                                                       \
+    l_run = l_run * corr + psum;                                                                              \
+    m_run = m_new;                                                                                            \
+    _Pragma("unroll") for (int dt = 0; dt < DH / 16; ++dt) {                                                  \
+      o[dt] *= corr;                                                                                          \
+      o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, va[B][dt]), pf, o[dt], 0, 0, 0); \
+    }                                                                                                         \
+  }
+  if (c0 < c1) ATT_LOAD(0, c0)
+  int ch = c0;
+  for (; ch + 2 <= c1; ch += 2) {
+    ATT_LOAD(1, ch + 1)
+    ATT_COMPUTE(0, ch)
+    if (ch + 2 < c1) ATT_LOAD(0, ch + 2)
+    ATT_COMPUTE(1, ch + 1)
+  }
+  if (ch < c1) ATT_COMPUTE(0, ch)
+#undef ATT_LOAD
+#undef ATT_COMPUTE
   l_run += __shfl_xor(l_run, 16);
   l_run += __shfl_xor(l_run, 32);
   if (valid) {
