@@ -144,9 +144,147 @@ __global__ __launch_bounds__(SAMP_THREADS) void sample_row_kernel(const float* _
   if (threadIdx.x == 0) tok_out[0] = tok;
 }
 
+// The same draw for vocabularies of up to 32768 ids with the row held in registers: wave w owns the ids
+// [w R 64, (w+1) R 64) (R = rows of 64 ids per wave), lane l of it the ids w R 64 + 64 k + l, so every load and
+// store is a coalesced 256-byte run and the logits are read once.  The inverse-CDF walk is three nested searches
+// in ascending id order, all sums in fp64: wave (scan of the 16 wave totals), row of 64 ids (scan of the wave's
+// row totals), lane (scan of the row).  The row totals come from one transposing butterfly (32 exchanges for 32
+// rows instead of 6 per row): each exchange halves the rows a lane still carries.
+#define SAMP_ROWS_MAX 32
+__device__ __forceinline__ double scan_up_d(double v, int lane, int width) {
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const double t = __shfl_up(v, o);
+    if (o < width && lane >= o) v += t;
+  }
+  return v;
+}
+__global__ __launch_bounds__(SAMP_THREADS) void sample_row_reg_kernel(const float* __restrict__ logits, int V, float mult,
+                                                                      float u, int R, float* __restrict__ q_out,
+                                                                      int* __restrict__ tok_out) {
+  __shared__ MaxIdx shm[SAMP_WAVES];
+  __shared__ double shd[SAMP_WAVES];
+  __shared__ double rt[SAMP_WAVES][SAMP_ROWS_MAX + 1];   // row totals, one padded line per wave
+  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int row0 = w * R * 64;           // first id of this wave
+  const int j0 = row0 + lane;
+  float e[SAMP_ROWS_MAX];
+  MaxIdx m;
+  m.v = -INFINITY; m.i = 0x7fffffff;
+#pragma unroll
+  for (int k = 0; k < SAMP_ROWS_MAX; ++k) {
+    const int j = j0 + 64 * k;
+    const bool in = k < R && j < V;
+    e[k] = in ? logits[j] : -INFINITY;
+    if (in && e[k] > m.v) { m.v = e[k]; m.i = j; }   // ids ascend with k: a strict test keeps the lowest id on ties
+  }
+  const MaxIdx top = block_argmax(m, shm);
+  const float zmax = top.v * mult;
+  float acc = 0.f;
+#pragma unroll
+  for (int k = 0; k < SAMP_ROWS_MAX; ++k) {
+    const int j = j0 + 64 * k;
+    // hardware exp2 (1 ulp) of a product rounded once: relative error below 1e-5 for exponents down to -100,
+    // two orders under what the bf16 logits carry
+    e[k] = (k < R && j < V) ? __expf(e[k] * mult - zmax) : 0.f;
+    acc += e[k];
+  }
+  const float sum = (float)block_sum_d((double)acc, shd);
+  const float inv = 1.0f / sum;
+#pragma unroll
+  for (int k = 0; k < SAMP_ROWS_MAX; ++k) {
+    const int j = j0 + 64 * k;
+    e[k] = e[k] * inv;
+    if (k < R && j < V) q_out[j] = e[k];
+  }
+  // transposing butterfly: after the exchange over lane bit b a lane carries half of its rows, summed over both
+  // partners; after bits 5..1 it carries row (lane >> 1), after bit 0 both lanes of a pair hold that row's total
+  double a[SAMP_ROWS_MAX / 2];
+  {
+    const bool hi = (lane & 32) != 0;
+#pragma unroll
+    for (int i = 0; i < SAMP_ROWS_MAX / 2; ++i) {
+      float x = e[i], y = e[i + SAMP_ROWS_MAX / 2];
+      asm volatile("" : "+v"(x), "+v"(y));      // keep the choice a select of values, not of register indices
+      const double send = (double)(hi ? x : y);
+      const double keep = (double)(hi ? y : x);
+      a[i] = keep + __shfl_xor(send, 32);
+    }
+  }
+#pragma unroll
+  for (int half = SAMP_ROWS_MAX / 4, off = 16; half >= 1; half >>= 1, off >>= 1) {
+    const bool hi = (lane & off) != 0;
+#pragma unroll
+    for (int i = 0; i < half; ++i) {
+      double x = a[i], y = a[i + half];
+      asm volatile("" : "+v"(x), "+v"(y));
+      const double send = hi ? x : y;
+      const double keep = hi ? y : x;
+      a[i] = keep + __shfl_xor(send, off);
+    }
+  }
+  a[0] += __shfl_xor(a[0], 1);
+  if ((lane & 1) == 0) rt[w][lane >> 1] = a[0];
+  __syncthreads();
+  // every wave: the 16 wave totals (lane i < 16 sums wave i's rows in order), their scan, the owner wave
+  double wt = 0.0;
+  if (lane < SAMP_WAVES) {
+    for (int k = 0; k < SAMP_ROWS_MAX; ++k) wt += rt[lane][k];
+  }
+  const double wincl = scan_up_d(wt, lane, SAMP_WAVES);
+  const double total = __shfl(wincl, SAMP_WAVES - 1);
+  if (!(total > 0.0)) {                  // no mass at all
+    if (threadIdx.x == 0) tok_out[0] = -1;
+    return;
+  }
+  const double target = (double)u * total;
+  const unsigned long long wmass = __ballot(lane < SAMP_WAVES && wt > 0.0);
+  const unsigned long long whit = __ballot(lane < SAMP_WAVES && wt > 0.0 && wincl > target);
+  // rounding can leave the target at or beyond the total: then the draw is the last id with mass
+  const bool clamp = whit == 0;
+  const int owner = clamp ? 63 - __clzll((long long)wmass) : __ffsll((long long)whit) - 1;
+  if (w != owner) return;
+  double wexcl = __shfl_up(wincl, 1);
+  if (lane == 0) wexcl = 0.0;
+  const double base = __shfl(wexcl, owner);
+  // the last id of this wave with mass (the fallback wherever rounding lets a search run off its end)
+  int lastpos = -1;
+#pragma unroll
+  for (int k = 0; k < SAMP_ROWS_MAX; ++k)
+    if (e[k] > 0.f) lastpos = j0 + 64 * k;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) lastpos = max(lastpos, __shfl_xor(lastpos, o));
+  // row search: lane k < 32 holds row k's total
+  const double rtk = lane < SAMP_ROWS_MAX ? rt[w][lane] : 0.0;
+  const double rincl = scan_up_d(rtk, lane, SAMP_ROWS_MAX);
+  const unsigned long long rhit = __ballot(lane < SAMP_ROWS_MAX && rtk > 0.0 && base + rincl > target);
+  int tok = lastpos;
+  if (!clamp && rhit) {
+    const int row = __ffsll((long long)rhit) - 1;
+    double rexcl = __shfl_up(rincl, 1);
+    if (lane == 0) rexcl = 0.0;
+    const double rbase = base + __shfl(rexcl, row);
+    float qf = 0.f;
+#pragma unroll
+    for (int k = 0; k < SAMP_ROWS_MAX; ++k) qf = (k == row) ? e[k] : qf;
+    const double qk = (double)qf;
+    const double incl = scan_up_d(qk, lane, 64);
+    const unsigned long long pos = __ballot(qk > 0.0);
+    const unsigned long long hit = __ballot(qk > 0.0 && rbase + incl > target);
+    const int l = hit ? __ffsll((long long)hit) - 1 : 63 - __clzll((long long)pos);   // pos != 0: the row has mass
+    tok = row0 + 64 * row + l;
+  }
+  if (lane == 0) tok_out[0] = tok;
+}
+
 hipError_t launch_sample_row(const float* logits, int V, float mult, int greedy, float u, float* q_out, int* tok_out,
                              hipStream_t st) {
-  sample_row_kernel<<<1, SAMP_THREADS, 0, st>>>(logits, V, mult, greedy, u, q_out, tok_out);
+  if (!greedy && V <= SAMP_ROWS_MAX * SAMP_THREADS) {
+    const int R = (V + SAMP_THREADS - 1) / SAMP_THREADS;   // rows of 64 ids per wave
+    sample_row_reg_kernel<<<1, SAMP_THREADS, 0, st>>>(logits, V, mult, u, R, q_out, tok_out);
+  } else {
+    sample_row_kernel<<<1, SAMP_THREADS, 0, st>>>(logits, V, mult, greedy, u, q_out, tok_out);
+  }
   return hipGetLastError();
 }
 
