@@ -63,7 +63,10 @@ def _logit_rows(n, v, seed, scale=3.0):
     return synth.normal_tensor((n, v), scale, seed, 77, torch.float32)
 
 
-@pytest.mark.parametrize("V,temp,ls", [(1024, 1.0, 8.0), (32000, 1.0, 1.0), (32256, 0.7, 1.0), (50, 1.0, 1.0)])
+# 32768 is the largest vocabulary of the register-resident kernel, 32769 and 50304 take the generic one; 4160 = 65
+# rows of 64 leaves ragged rows in every wave
+@pytest.mark.parametrize("V,temp,ls", [(1024, 1.0, 8.0), (32000, 1.0, 1.0), (32256, 0.7, 1.0), (50, 1.0, 1.0),
+                                       (32768, 1.0, 1.0), (32769, 1.0, 1.0), (50304, 1.3, 1.0), (4160, 0.5, 2.0)])
 def test_draft_sampling_matches_oracle(V, temp, ls):
     amd = _amd()
     rows = _logit_rows(6, V, 5)
@@ -80,6 +83,30 @@ def test_draft_sampling_matches_oracle(V, temp, ls):
             assert tok == sampling.sample(q, us[i])
             n_checked += 1
     assert n_checked >= 4
+
+
+@pytest.mark.parametrize("V", [32000, 777, 40000])
+def test_draft_sampling_walk_on_sparse_rows_and_extreme_uniforms(V):
+    """Very peaked rows (most probabilities underflow to exactly 0) and uniforms at both ends of [0, 1): the draw
+    must be the first id whose fp64 running sum of the kernel's own q row exceeds u times the total, never an id of
+    zero probability."""
+    amd = _amd()
+    rows = _logit_rows(4, V, 9, scale=60.0)
+    rows[3, :] = -1000.0
+    rows[3, V - 3] = 5.0                                   # a single id carries all the mass
+    n_checked = 0
+    for i in range(4):
+        for u in (0.0, 1e-7, 0.37, 0.5, 0.93, 1.0 - 2.0 ** -24):
+            q_gpu, tok = amd.sample_row(rows[i].cuda(), 1.0, 1.0, u)
+            q = q_gpu.cpu().numpy().astype(np.float64)
+            assert q[tok] > 0.0
+            cdf = np.cumsum(q)
+            want = int(np.searchsorted(cdf, np.float64(np.float32(u)) * cdf[-1], side="right"))
+            margin = np.min(np.abs(cdf / cdf[-1] - u)[q > 0])
+            if margin > 1e-9:
+                assert tok == want, (i, u, tok, want)
+                n_checked += 1
+    assert n_checked >= 16
 
 
 def test_greedy_sampling_is_argmax_with_lowest_id_ties():
