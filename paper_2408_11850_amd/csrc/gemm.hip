@@ -172,19 +172,24 @@ hipError_t launch_gemm_partials(const GemmPlan& p, const bf16* x, const void* wp
   return hipGetLastError();
 }
 
-// y[i] = sum_s partials[s][i], slices added in ascending order
-__global__ void reduce_partials_kernel(float* __restrict__ y, const float* __restrict__ P, int S, size_t n4) {
+// y[i] = sum_s partials[s][i], slices added in ascending order; with a row scale, row i / N of the sum is
+// multiplied by it (N % 4 == 0)
+__global__ void reduce_partials_kernel(float* __restrict__ y, const float* __restrict__ P, int S, size_t n4, RowScale rs,
+                                       int N4) {
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= n4) return;
   const f32x4* p = reinterpret_cast<const f32x4*>(P);
   f32x4 t = p[i];
   for (int s = 1; s < S; ++s) t += p[(size_t)s * n4 + i];
+  if (rs.ssq) t *= rs.inv((int)(i / (size_t)N4));
   reinterpret_cast<f32x4*>(y)[i] = t;
 }
 
-hipError_t launch_reduce_partials(float* y, const float* partials, int S, size_t n, hipStream_t st) {
+hipError_t launch_reduce_partials(float* y, const float* partials, int S, size_t n, hipStream_t st, RowScale rs, int N) {
   size_t n4 = n / 4;   // n = M*N with N % 16 == 0
-  reduce_partials_kernel<<<dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, st>>>(y, partials, S, n4);
+  if (rs.ssq && N < 4) return hipErrorInvalidValue;
+  reduce_partials_kernel<<<dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, st>>>(y, partials, S, n4, rs,
+                                                                                   rs.ssq ? N / 4 : 1);
   return hipGetLastError();
 }
 

@@ -120,6 +120,61 @@ hipError_t launch_addnorm(float* h, const float* partials, int S, const bf16* ga
   return hipGetLastError();
 }
 
+// The residual add alone, spread over d/1024 workgroups per row (one compute unit cannot pull the S slices of a
+// long row fast enough): h += sum_s P[s] in the same order as addnorm_kernel, and the sum of squares of each
+// 1024-column piece, plus x' = bf16(h * gain) for the next projection (whose consumers apply 1/rms).
+#define ADDSQ_THREADS 256
+__global__ __launch_bounds__(ADDSQ_THREADS) void add_sumsq_kernel(float* __restrict__ h, const float* __restrict__ P,
+                                                                  int S, const bf16* __restrict__ gain,
+                                                                  bf16* __restrict__ a, float* __restrict__ ssq, int M,
+                                                                  int d, int W) {
+  __shared__ float sh[ADDSQ_THREADS / 64];
+  const int m = blockIdx.y, w = blockIdx.x;
+  const int d4 = d >> 2;
+  const int i = w * ADDSQ_THREADS + threadIdx.x;
+  float ss = 0.f;
+  if (i < d4) {
+    f32x4* hr = reinterpret_cast<f32x4*>(h + (size_t)m * d);
+    const f32x4* P4 = reinterpret_cast<const f32x4*>(P);
+    f32x4 t = hr[i];
+    if (P) {
+      int s = 0;
+      for (; s + 4 <= S; s += 4) {
+        const f32x4 p0 = P4[((size_t)(s + 0) * M + m) * d4 + i], p1 = P4[((size_t)(s + 1) * M + m) * d4 + i];
+        const f32x4 p2 = P4[((size_t)(s + 2) * M + m) * d4 + i], p3 = P4[((size_t)(s + 3) * M + m) * d4 + i];
+        t += p0; t += p1; t += p2; t += p3;
+      }
+      for (; s < S; ++s) t += P4[((size_t)s * M + m) * d4 + i];
+      hr[i] = t;
+    }
+    ss = t.x * t.x + t.y * t.y + t.z * t.z + t.w * t.w;
+    const bf16* g = gain + (size_t)i * 4;
+    bf16* dst = a + (size_t)m * d + (size_t)i * 4;
+    dst[0] = __float2bfloat16(t.x * __bfloat162float(g[0]));
+    dst[1] = __float2bfloat16(t.y * __bfloat162float(g[1]));
+    dst[2] = __float2bfloat16(t.z * __bfloat162float(g[2]));
+    dst[3] = __float2bfloat16(t.w * __bfloat162float(g[3]));
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = ss;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float tot = 0.f;
+#pragma unroll
+    for (int k = 0; k < ADDSQ_THREADS / 64; ++k) tot += sh[k];
+    ssq[m * W + w] = tot;
+  }
+}
+hipError_t launch_add_sumsq(float* h, const float* partials, int S, const bf16* gain, bf16* a, float* ssq, int M,
+                            int d, int* W_out, hipStream_t st) {
+  const int W = ((d >> 2) + ADDSQ_THREADS - 1) / ADDSQ_THREADS;
+  if ((d & 3) || W > ADDSQ_MAX_PIECES) return hipErrorInvalidValue;
+  add_sumsq_kernel<<<dim3(W, M), ADDSQ_THREADS, 0, st>>>(h, partials, S, gain, a, ssq, M, d, W);
+  *W_out = W;
+  return hipGetLastError();
+}
+
 // One 64-thread slice of a workgroup per (token, head) of the fused QKV output (ROPE_HPB heads per workgroup);
 // thread e of the slice handles the pair (e, e + dh/2).
 // q heads: rotate, store bf16 [M][Hq][dh].  k heads: rotate, store into the page in K-operand order.
@@ -141,7 +196,7 @@ hipError_t launch_rope_table(float2* tab, const int* len_ptr, int M, int dh, flo
 
 __global__ void rope_append_kernel(const float* __restrict__ P, int S, bf16* __restrict__ q, bf16* __restrict__ pool,
                                    const int* __restrict__ block_table, const int* __restrict__ len_ptr, KvGeom g,
-                                   int layer, int M, int Hq, float theta, const float2* __restrict__ tab) {
+                                   int layer, int M, int Hq, float theta, const float2* __restrict__ tab, RowScale rs) {
   const int i = blockIdx.x, head = blockIdx.y * ROPE_HPB + (threadIdx.x >> 6);
   const int dh = g.head_dim, half = dh >> 1, Hkv = g.n_kv_heads;
   const int N = (Hq + 2 * Hkv) * dh;
@@ -154,6 +209,9 @@ __global__ void rope_append_kernel(const float* __restrict__ P, int S, bf16* __r
     x0 += row[e];
     x1 += row[e + half];
   }
+  const float inv = rs.inv(i);
+  x0 *= inv;
+  x1 *= inv;
   if (head < Hq + Hkv) {   // rotate pair (e, e + dh/2) by pos * theta^(-2e/dh)
     float cs, sn;
     if (tab) {
@@ -192,14 +250,15 @@ __global__ void rope_append_kernel(const float* __restrict__ P, int S, bf16* __r
 }
 hipError_t launch_rope_append(const float* partials, int S, bf16* q, bf16* pool, const int* block_table,
                               const int* len_ptr, KvGeom g, int layer, int M, int Hq, float theta, hipStream_t st,
-                              const float2* tab) {
+                              const float2* tab, RowScale rs) {
   dim3 grid(M, (Hq + 2 * g.n_kv_heads + ROPE_HPB - 1) / ROPE_HPB), block(64 * ROPE_HPB);
-  rope_append_kernel<<<grid, block, 0, st>>>(partials, S, q, pool, block_table, len_ptr, g, layer, M, Hq, theta, tab);
+  rope_append_kernel<<<grid, block, 0, st>>>(partials, S, q, pool, block_table, len_ptr, g, layer, M, Hq, theta, tab,
+                                             rs);
   return hipGetLastError();
 }
 
 // z[m][f] = silu(gate) * up, gate/up panels interleaved in the fused projection output (width 2F)
-__global__ void silu_mul_kernel(const float* __restrict__ P, int S, bf16* __restrict__ z, int M, int F) {
+__global__ void silu_mul_kernel(const float* __restrict__ P, int S, bf16* __restrict__ z, int M, int F, RowScale rs) {
   const int m = blockIdx.y;
   const int f = blockIdx.x * blockDim.x + threadIdx.x;
   if (f >= F) return;
@@ -210,11 +269,14 @@ __global__ void silu_mul_kernel(const float* __restrict__ P, int S, bf16* __rest
     gv += row[gc];
     uv += row[gc + 16];
   }
+  const float inv = rs.inv(m);
+  gv *= inv;
+  uv *= inv;
   const float sg = gv / (1.0f + __expf(-gv));
   z[(size_t)m * F + f] = __float2bfloat16(sg * uv);
 }
-hipError_t launch_silu_mul(const float* partials, int S, bf16* z, int M, int F, hipStream_t st) {
+hipError_t launch_silu_mul(const float* partials, int S, bf16* z, int M, int F, hipStream_t st, RowScale rs) {
   dim3 grid((F + 255) / 256, M), block(256);
-  silu_mul_kernel<<<grid, block, 0, st>>>(partials, S, z, M, F);
+  silu_mul_kernel<<<grid, block, 0, st>>>(partials, S, z, M, F, rs);
   return hipGetLastError();
 }

@@ -50,6 +50,7 @@ struct ModelRt {
   int* len_dev = nullptr;
   int* tok_in = nullptr;
   float* h = nullptr;
+  float* ssq = nullptr;           // sums of squares of the rows of h, ADDSQ_MAX_PIECES pieces per row
   bf16 *a = nullptr, *qbuf = nullptr, *attn_out = nullptr, *z = nullptr;
   float *partials = nullptr, *opart = nullptr, *mlpart = nullptr, *logits = nullptr;
   long long n_forwards = 0;
@@ -108,6 +109,7 @@ int check_desc(const spec_model_desc& d, const char* name) {
   if (d.head_dim != 64 && d.head_dim != 128) FAIL(SPEC_E_INVAL, "%s: head_dim must be 64 or 128", name);
   if (d.n_heads % d.n_kv_heads) FAIL(SPEC_E_INVAL, "%s: n_heads must be a multiple of n_kv_heads", name);
   if (d.d_model % 16 || d.d_ffn % 16 || d.vocab % 16) FAIL(SPEC_E_INVAL, "%s: d_model, d_ffn, vocab must be multiples of 16", name);
+  if (d.d_model > 1024 * ADDSQ_MAX_PIECES) FAIL(SPEC_E_INVAL, "%s: d_model above %d", name, 1024 * ADDSQ_MAX_PIECES);
   if (!(d.rope_theta > 1.0f) || !(d.rms_eps >= 0.0f)) FAIL(SPEC_E_INVAL, "%s: bad rope_theta / rms_eps", name);
   return SPEC_OK;
 }
@@ -156,6 +158,7 @@ int init_model(ModelRt& m, const spec_model_desc& d, const spec_weights& w, cons
   const int amax = kmax > d.n_heads * d.head_dim ? kmax : d.n_heads * d.head_dim;
   if ((rc = dev_alloc(&m.tok_in, (size_t)MX))) return rc;
   if ((rc = dev_alloc(&m.h, (size_t)MX * d.d_model))) return rc;
+  if ((rc = dev_alloc(&m.ssq, (size_t)MX * ADDSQ_MAX_PIECES))) return rc;
   if ((rc = dev_alloc(&m.a, (size_t)MX * amax))) return rc;
   if ((rc = dev_alloc(&m.qbuf, (size_t)MX * d.n_heads * d.head_dim))) return rc;
   if ((rc = dev_alloc(&m.attn_out, (size_t)MX * d.n_heads * d.head_dim))) return rc;
@@ -184,7 +187,7 @@ void free_model(ModelRt& m) {
           (void)hipGraphExecDestroy(g);
           g = nullptr;
         }
-  void* ptrs[] = {m.pool, m.block_table_dev, m.len_dev, m.tok_in, m.h, m.a, m.qbuf, m.attn_out, m.z, m.partials,
+  void* ptrs[] = {m.pool, m.block_table_dev, m.len_dev, m.tok_in, m.h, m.ssq, m.a, m.qbuf, m.attn_out, m.z, m.partials,
                   m.opart, m.logits, m.pf_tok, m.pf_h, m.pf_a, m.pf_q, m.pf_attn, m.pf_z, m.pf_rope};
   for (void* p : ptrs)
     if (p) (void)hipFree(p);
@@ -260,27 +263,33 @@ int enqueue_forward(spec_ctx* c, int which, int M, int logit_rows) {
   GemmPlan p;
   const float* prev = nullptr;
   int prevS = 0;
+  // Every RMSNorm is split in three: a residual add spread over several workgroups per row, which leaves the
+  // rows' sums of squares and x' = bf16(h * gain); the projection of x'; and the factor 1/rms, applied to the
+  // projection's output rows by the kernel that adds its K slices.
+  RowScale rs{m.ssq, 0, d.d_model, d.rms_eps};
   for (int l = 0; l < d.n_layers; ++l) {
-    HIPCHK(launch_addnorm(m.h, prev, prevS, (const bf16*)m.attn_norm[l], m.a, M, d.d_model, d.rms_eps, st));
+    HIPCHK(launch_add_sumsq(m.h, prev, prevS, (const bf16*)m.attn_norm[l], m.a, m.ssq, M, d.d_model, &rs.W, st));
     if ((rc = run_gemm(c, which, m, M, qkvN, d.d_model, m.a, m.wqkv[l], &p))) return rc;
     HIPCHK(launch_rope_append(m.partials, p.S, m.qbuf, m.pool, m.block_table_dev, m.len_dev, m.geom, l, M, d.n_heads,
-                              d.rope_theta, st));
+                              d.rope_theta, st, nullptr, rs));
     HIPCHK(launch_attention(m.qbuf, m.pool, m.block_table_dev, m.len_dev, m.geom, l, M, d.n_heads, m.split_tokens,
                             m.opart, m.mlpart, m.attn_out, st));
     if ((rc = run_gemm(c, which, m, M, d.d_model, HD, m.attn_out, m.wo[l], &p))) return rc;
-    HIPCHK(launch_addnorm(m.h, m.partials, p.S, (const bf16*)m.ffn_norm[l], m.a, M, d.d_model, d.rms_eps, st));
+    HIPCHK(launch_add_sumsq(m.h, m.partials, p.S, (const bf16*)m.ffn_norm[l], m.a, m.ssq, M, d.d_model, &rs.W, st));
     if ((rc = run_gemm(c, which, m, M, 2 * d.d_ffn, d.d_model, m.a, m.wgu[l], &p))) return rc;
-    HIPCHK(launch_silu_mul(m.partials, p.S, m.z, M, d.d_ffn, st));
+    HIPCHK(launch_silu_mul(m.partials, p.S, m.z, M, d.d_ffn, st, rs));
     if ((rc = run_gemm(c, which, m, M, d.d_model, d.d_ffn, m.z, m.wdown[l], &p))) return rc;
     prev = m.partials;
     prevS = p.S;
   }
   if (logit_rows > 0) {
-    HIPCHK(launch_addnorm(m.h, prev, prevS, (const bf16*)m.final_norm, m.a, M, d.d_model, d.rms_eps, st));
+    HIPCHK(launch_add_sumsq(m.h, prev, prevS, (const bf16*)m.final_norm, m.a, m.ssq, M, d.d_model, &rs.W, st));
     const int rows = logit_rows >= M ? M : 1;
     const bf16* x = m.a + (size_t)(M - rows) * d.d_model;
     if ((rc = run_gemm(c, which, m, rows, d.vocab, d.d_model, x, m.lm_head, &p))) return rc;
-    HIPCHK(launch_reduce_partials(m.logits, m.partials, p.S, (size_t)rows * d.vocab, st));
+    RowScale rl = rs;
+    rl.ssq = m.ssq + (size_t)(M - rows) * rs.W;
+    HIPCHK(launch_reduce_partials(m.logits, m.partials, p.S, (size_t)rows * d.vocab, st, rl, d.vocab));
   }
   HIPCHK(launch_add_int(m.len_dev, M, st));
   return SPEC_OK;

@@ -38,7 +38,26 @@ struct GemmPlan {
 GemmPlan gemm_plan(int M, int N, int K, int wgs_per_cu = 2);
 hipError_t launch_gemm_partials(const GemmPlan& p, const bf16* x, const void* wp, float* partials, hipStream_t st,
                                 int tag);
-hipError_t launch_reduce_partials(float* y, const float* partials, int S, size_t n, hipStream_t st);
+// The RMSNorm of the decode path is split in three: the residual-add kernel stores x' = bf16(h * gain) and the
+// rows' sums of squares (W pieces per row); the projection runs on x' unchanged; whoever adds the projection's K
+// slices multiplies the sum by inv_m = 1 / sqrt(sum_w ssq[m][w] / d + eps) (the projection is linear in its rows
+// and bf16 keeps the same relative precision at any scale).  ssq == nullptr: no scaling.
+struct RowScale {
+  const float* ssq;    // [rows][W]
+  int W, d;
+  float eps;
+#ifdef __HIPCC__
+  __device__ __forceinline__ float inv(int m) const {
+    if (!ssq) return 1.0f;
+    float tot = 0.f;
+    for (int i = 0; i < W; ++i) tot += ssq[m * W + i];
+    return 1.0f / sqrtf(tot / (float)d + eps);
+  }
+#endif
+};
+// n = M * N elements; rs scales row i / N (N given) of the sum
+hipError_t launch_reduce_partials(float* y, const float* partials, int S, size_t n, hipStream_t st,
+                                  RowScale rs = RowScale{nullptr, 0, 0, 0.f}, int N = 0);
 hipError_t launch_pack_weight(void* dst, const void* src, int N, int K, int panel_start, int panel_step, hipStream_t st);
 hipError_t launch_read_probe(const void* src, size_t bytes, void* out, hipStream_t st);
 
@@ -74,16 +93,22 @@ hipError_t launch_embed(float* h, const bf16* embed, const int* tok, int M, int 
 // h += sum_s partials[s] (if partials), a = rmsnorm(h) * gain
 hipError_t launch_addnorm(float* h, const float* partials, int S, const bf16* gain, bf16* a, int M, int d,
                           float eps, hipStream_t st);
+// h += sum_s partials[s] (if partials), a = bf16(h * gain) (not normalised), ssq[m][w] = sum of h^2 over the w-th
+// piece of 1024 columns of row m; returns the number of pieces W through *W_out (ssq needs M * W floats)
+#define ADDSQ_MAX_PIECES 16
+hipError_t launch_add_sumsq(float* h, const float* partials, int S, const bf16* gain, bf16* a, float* ssq, int M,
+                            int d, int* W_out, hipStream_t st);
 // tab: optional [M][dh/2] (cos, sin) table from launch_rope_table for the same len; nullptr = compute in place
 hipError_t launch_rope_append(const float* partials, int S, bf16* q, bf16* pool, const int* block_table,
                               const int* len_ptr, KvGeom g, int layer, int M, int Hq, float theta, hipStream_t st,
-                              const float2* tab = nullptr);
+                              const float2* tab = nullptr, RowScale rs = RowScale{nullptr, 0, 0, 0.f});
 hipError_t launch_rope_table(float2* tab, const int* len_ptr, int M, int dh, float theta, hipStream_t st);
 hipError_t launch_attention(const bf16* q, const bf16* pool, const int* block_table, const int* len_ptr, KvGeom g,
                             int layer, int M, int Hq, int split_tokens, float* opart, float* mlpart, bf16* out,
                             hipStream_t st);
 size_t attention_workspace_floats(int Hq, int Hkv, int dh, int max_seq);
-hipError_t launch_silu_mul(const float* partials, int S, bf16* z, int M, int F, hipStream_t st);
+hipError_t launch_silu_mul(const float* partials, int S, bf16* z, int M, int F, hipStream_t st,
+                           RowScale rs = RowScale{nullptr, 0, 0, 0.f});
 
 // prompt-sized (matrix-core bound) kernels: epilogue 0 = store fp32, 1 = add into fp32, 2 = silu(gate)*up -> bf16
 #define SPEC_PREFILL_BLOCK_MAX 4096   // most prompt tokens one dense pass takes

@@ -125,7 +125,10 @@ def test_full_depth_pair_properties_in_benchmark_configuration():
         row = ctx.verify([prompt[-1]] + a[:i], want_logits=True)[-1]
         gap = abs(float(row[a[i]]) - float(row[b[i]])) / float(row.max() - row.min())
         print(f"  algo {other} parts from AR at token {i}: logit gap {gap:.2e} of the range", flush=True)
-        assert gap < 6e-2 and min(row[a[i]], row[b[i]]) >= np.sort(row)[-2] - 1e-6
+        # both choices sit within the evaluation-order noise of the row's maximum (they need not be its top two:
+        # a third logit can lie between them)
+        top_gap = (float(row.max()) - min(float(row[a[i]]), float(row[b[i]]))) / float(row.max() - row.min())
+        assert gap < 6e-2 and top_gap < 6e-2
     # (3b) the two prompt paths fill equivalent caches: `multi` came after the matrix-core prompt pass (the default
     # for this shape); the same verify after 128 verify-sized prompt forwards is another bf16 evaluation order
     ctx.set_option(amd.SPEC_OPT_PREFILL, 0)
@@ -133,7 +136,12 @@ def test_full_depth_pair_properties_in_benchmark_configuration():
     chunked = ctx.verify(toks, want_logits=True)
     err = _rel_err(multi, chunked)
     print(f"  dense vs chunked prompt pass: {err:.2e} of the logit range", flush=True)
-    assert err < 6e-2
+    # Here every one of the 4095 cached K / V rows differs in rounding between the two runs, not only the new
+    # tokens' rows as in (1).  Bound: two independent bf16 evaluation orders, each sqrt(80 / 2) times the 6e-3 ..
+    # 8e-3 that 2 layers of these widths show against the fp64 oracle, i.e. sqrt(2) * 6.3 * 8e-3 = 7e-2 for a
+    # typical logit, and this is the maximum over 7 x 32000 of them (observed 3.4e-2 and 7.7e-2 with two
+    # different, equally accurate, orders of the RMSNorm arithmetic).
+    assert err < 1.5e-1
     ctx.close()
     # (4) sampled PEARL: overlapped streams == one stream, bit for bit
     res = []
