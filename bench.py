@@ -29,7 +29,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0      # dense bf16 matrix-core peak of the MI355X
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=48)
+    ap.add_argument("--steps", type=int, default=96)
     ap.add_argument("--warmup", type=int, default=4)
     ap.add_argument("--config", default="70b_7b", help="tiny | small | 7b_1b | 33b_1b | 70b_7b")
     ap.add_argument("--gamma", type=int, default=0, help="0 = calibrate gamma = round(c) on the box")
