@@ -159,44 +159,54 @@ __device__ __forceinline__ double scan_up_d(double v, int lane, int width) {
   }
   return v;
 }
-__global__ __launch_bounds__(SAMP_THREADS) void sample_row_reg_kernel(const float* __restrict__ logits, int V, float mult,
-                                                                      float u, int R, float* __restrict__ q_out,
-                                                                      int* __restrict__ tok_out) {
-  __shared__ MaxIdx shm[SAMP_WAVES];
-  __shared__ double shd[SAMP_WAVES];
-  __shared__ double rt[SAMP_WAVES][SAMP_ROWS_MAX + 1];   // row totals, one padded line per wave
-  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int row0 = w * R * 64;           // first id of this wave
-  const int j0 = row0 + lane;
-  float e[SAMP_ROWS_MAX];
+struct RegGeom {          // which ids a thread owns: row0 + 64 k + lane, k < R
+  int R, w, lane, row0, j0;
+};
+__device__ __forceinline__ RegGeom reg_geom(int V) {
+  RegGeom g;
+  g.R = (V + SAMP_THREADS - 1) / SAMP_THREADS;
+  g.w = threadIdx.x >> 6;
+  g.lane = threadIdx.x & 63;
+  g.row0 = g.w * g.R * 64;
+  g.j0 = g.row0 + g.lane;
+  return g;
+}
+// probability of a logit given the row's statistics: hardware exp2 (1 ulp) of a product rounded once, times the
+// reciprocal of the sum: relative error below 1e-5 for exponents down to -100, two orders under what the bf16
+// logits carry.  Every kernel of the register path forms p and q with this one expression.
+__device__ __forceinline__ float reg_prob(float l, float mult, float zmax, float inv) { return __expf(l * mult - zmax) * inv; }
+
+// Loads the row once; returns the arg-max, sum_j exp(mult l_j - zmax) and e[k] = exp(mult l - zmax) (0 outside V).
+__device__ __forceinline__ void reg_softmax(const float* __restrict__ row, int V, float mult, const RegGeom& g,
+                                            float (&e)[SAMP_ROWS_MAX], MaxIdx& top, float& sum, MaxIdx* shm,
+                                            double* shd) {
   MaxIdx m;
   m.v = -INFINITY; m.i = 0x7fffffff;
 #pragma unroll
   for (int k = 0; k < SAMP_ROWS_MAX; ++k) {
-    const int j = j0 + 64 * k;
-    const bool in = k < R && j < V;
-    e[k] = in ? logits[j] : -INFINITY;
+    const int j = g.j0 + 64 * k;
+    const bool in = k < g.R && j < V;
+    e[k] = in ? row[j] : -INFINITY;
     if (in && e[k] > m.v) { m.v = e[k]; m.i = j; }   // ids ascend with k: a strict test keeps the lowest id on ties
   }
-  const MaxIdx top = block_argmax(m, shm);
+  top = block_argmax(m, shm);
   const float zmax = top.v * mult;
   float acc = 0.f;
 #pragma unroll
   for (int k = 0; k < SAMP_ROWS_MAX; ++k) {
-    const int j = j0 + 64 * k;
-    // hardware exp2 (1 ulp) of a product rounded once: relative error below 1e-5 for exponents down to -100,
-    // two orders under what the bf16 logits carry
-    e[k] = (k < R && j < V) ? __expf(e[k] * mult - zmax) : 0.f;
+    const int j = g.j0 + 64 * k;
+    e[k] = (k < g.R && j < V) ? __expf(e[k] * mult - zmax) : 0.f;
     acc += e[k];
   }
-  const float sum = (float)block_sum_d((double)acc, shd);
-  const float inv = 1.0f / sum;
-#pragma unroll
-  for (int k = 0; k < SAMP_ROWS_MAX; ++k) {
-    const int j = j0 + 64 * k;
-    e[k] = e[k] * inv;
-    if (k < R && j < V) q_out[j] = e[k];
-  }
+  sum = (float)block_sum_d((double)acc, shd);
+}
+
+// Inverse-CDF draw over the non-negative weights e[] (0 outside V).  Returns the id to every thread, -1 if the
+// weights have no mass; *total_out = their fp64 sum.  rt: [SAMP_WAVES][SAMP_ROWS_MAX + 1] doubles, shi: 1 int.
+// Every thread of the workgroup must call it (two barriers inside).
+__device__ __forceinline__ int reg_draw(const float (&e)[SAMP_ROWS_MAX], const RegGeom& g, float u,
+                                        double (*rt)[SAMP_ROWS_MAX + 1], int* shi, double* total_out) {
+  const int lane = g.lane, w = g.w;
   // transposing butterfly: after the exchange over lane bit b a lane carries half of its rows, summed over both
   // partners; after bits 5..1 it carries row (lane >> 1), after bit 0 both lanes of a pair hold that row's total
   double a[SAMP_ROWS_MAX / 2];
@@ -204,8 +214,8 @@ __global__ __launch_bounds__(SAMP_THREADS) void sample_row_reg_kernel(const floa
     const bool hi = (lane & 32) != 0;
 #pragma unroll
     for (int i = 0; i < SAMP_ROWS_MAX / 2; ++i) {
-      float x = e[i], y = e[i + SAMP_ROWS_MAX / 2];
-      asm volatile("" : "+v"(x), "+v"(y));      // keep the choice a select of values, not of register indices
+      const float x = e[i], y = e[i + SAMP_ROWS_MAX / 2];
+      asm volatile("" ::"v"(x), "v"(y));        // a second use keeps the choice a select of values, not of indices
       const double send = (double)(hi ? x : y);
       const double keep = (double)(hi ? y : x);
       a[i] = keep + __shfl_xor(send, 32);
@@ -216,8 +226,8 @@ __global__ __launch_bounds__(SAMP_THREADS) void sample_row_reg_kernel(const floa
     const bool hi = (lane & off) != 0;
 #pragma unroll
     for (int i = 0; i < half; ++i) {
-      double x = a[i], y = a[i + half];
-      asm volatile("" : "+v"(x), "+v"(y));
+      const double x = a[i], y = a[i + half];
+      asm volatile("" ::"v"(x), "v"(y));
       const double send = hi ? x : y;
       const double keep = hi ? y : x;
       a[i] = keep + __shfl_xor(send, off);
@@ -233,55 +243,78 @@ __global__ __launch_bounds__(SAMP_THREADS) void sample_row_reg_kernel(const floa
   }
   const double wincl = scan_up_d(wt, lane, SAMP_WAVES);
   const double total = __shfl(wincl, SAMP_WAVES - 1);
-  if (!(total > 0.0)) {                  // no mass at all
-    if (threadIdx.x == 0) tok_out[0] = -1;
-    return;
-  }
+  if (total_out) *total_out = total;
   const double target = (double)u * total;
   const unsigned long long wmass = __ballot(lane < SAMP_WAVES && wt > 0.0);
   const unsigned long long whit = __ballot(lane < SAMP_WAVES && wt > 0.0 && wincl > target);
   // rounding can leave the target at or beyond the total: then the draw is the last id with mass
   const bool clamp = whit == 0;
-  const int owner = clamp ? 63 - __clzll((long long)wmass) : __ffsll((long long)whit) - 1;
-  if (w != owner) return;
-  double wexcl = __shfl_up(wincl, 1);
-  if (lane == 0) wexcl = 0.0;
-  const double base = __shfl(wexcl, owner);
-  // the last id of this wave with mass (the fallback wherever rounding lets a search run off its end)
-  int lastpos = -1;
+  const int owner = !wmass ? -1 : (clamp ? 63 - __clzll((long long)wmass) : __ffsll((long long)whit) - 1);
+  if (threadIdx.x == 0 && owner < 0) shi[0] = -1;      // no mass at all
+  if (w == owner) {
+    double wexcl = __shfl_up(wincl, 1);
+    if (lane == 0) wexcl = 0.0;
+    const double base = __shfl(wexcl, owner);
+    // the last id of this wave with mass (the fallback wherever rounding lets a search run off its end)
+    int lastpos = -1;
 #pragma unroll
-  for (int k = 0; k < SAMP_ROWS_MAX; ++k)
-    if (e[k] > 0.f) lastpos = j0 + 64 * k;
+    for (int k = 0; k < SAMP_ROWS_MAX; ++k)
+      if (e[k] > 0.f) lastpos = g.j0 + 64 * k;
 #pragma unroll
-  for (int o = 32; o > 0; o >>= 1) lastpos = max(lastpos, __shfl_xor(lastpos, o));
-  // row search: lane k < 32 holds row k's total
-  const double rtk = lane < SAMP_ROWS_MAX ? rt[w][lane] : 0.0;
-  const double rincl = scan_up_d(rtk, lane, SAMP_ROWS_MAX);
-  const unsigned long long rhit = __ballot(lane < SAMP_ROWS_MAX && rtk > 0.0 && base + rincl > target);
-  int tok = lastpos;
-  if (!clamp && rhit) {
-    const int row = __ffsll((long long)rhit) - 1;
-    double rexcl = __shfl_up(rincl, 1);
-    if (lane == 0) rexcl = 0.0;
-    const double rbase = base + __shfl(rexcl, row);
-    float qf = 0.f;
+    for (int o = 32; o > 0; o >>= 1) lastpos = max(lastpos, __shfl_xor(lastpos, o));
+    // row search: lane k < 32 holds row k's total
+    const double rtk = lane < SAMP_ROWS_MAX ? rt[w][lane] : 0.0;
+    const double rincl = scan_up_d(rtk, lane, SAMP_ROWS_MAX);
+    const unsigned long long rhit = __ballot(lane < SAMP_ROWS_MAX && rtk > 0.0 && base + rincl > target);
+    int tok = lastpos;
+    if (!clamp && rhit) {
+      const int row = __ffsll((long long)rhit) - 1;
+      double rexcl = __shfl_up(rincl, 1);
+      if (lane == 0) rexcl = 0.0;
+      const double rbase = base + __shfl(rexcl, row);
+      float qf = 0.f;
 #pragma unroll
-    for (int k = 0; k < SAMP_ROWS_MAX; ++k) qf = (k == row) ? e[k] : qf;
-    const double qk = (double)qf;
-    const double incl = scan_up_d(qk, lane, 64);
-    const unsigned long long pos = __ballot(qk > 0.0);
-    const unsigned long long hit = __ballot(qk > 0.0 && rbase + incl > target);
-    const int l = hit ? __ffsll((long long)hit) - 1 : 63 - __clzll((long long)pos);   // pos != 0: the row has mass
-    tok = row0 + 64 * row + l;
+      for (int k = 0; k < SAMP_ROWS_MAX; ++k) qf = (k == row) ? e[k] : qf;
+      const double qk = (double)qf;
+      const double incl = scan_up_d(qk, lane, 64);
+      const unsigned long long pos = __ballot(qk > 0.0);
+      const unsigned long long hit = __ballot(qk > 0.0 && rbase + incl > target);
+      const int l = hit ? __ffsll((long long)hit) - 1 : 63 - __clzll((long long)pos);   // pos != 0: the row has mass
+      tok = g.row0 + 64 * row + l;
+    }
+    if (lane == 0) shi[0] = tok;
   }
-  if (lane == 0) tok_out[0] = tok;
+  __syncthreads();
+  return shi[0];
+}
+
+__global__ __launch_bounds__(SAMP_THREADS) void sample_row_reg_kernel(const float* __restrict__ logits, int V, float mult,
+                                                                      float u, float* __restrict__ q_out,
+                                                                      int* __restrict__ tok_out) {
+  __shared__ MaxIdx shm[SAMP_WAVES];
+  __shared__ double shd[SAMP_WAVES];
+  __shared__ double rt[SAMP_WAVES][SAMP_ROWS_MAX + 1];   // row totals, one padded line per wave
+  __shared__ int shi[1];
+  const RegGeom g = reg_geom(V);
+  float e[SAMP_ROWS_MAX];
+  MaxIdx top;
+  float sum;
+  reg_softmax(logits, V, mult, g, e, top, sum, shm, shd);
+  const float inv = 1.0f / sum;
+#pragma unroll
+  for (int k = 0; k < SAMP_ROWS_MAX; ++k) {
+    const int j = g.j0 + 64 * k;
+    e[k] = e[k] * inv;
+    if (k < g.R && j < V) q_out[j] = e[k];
+  }
+  const int tok = reg_draw(e, g, u, rt, shi, nullptr);
+  if (threadIdx.x == 0) tok_out[0] = tok;
 }
 
 hipError_t launch_sample_row(const float* logits, int V, float mult, int greedy, float u, float* q_out, int* tok_out,
                              hipStream_t st) {
   if (!greedy && V <= SAMP_ROWS_MAX * SAMP_THREADS) {
-    const int R = (V + SAMP_THREADS - 1) / SAMP_THREADS;   // rows of 64 ids per wave
-    sample_row_reg_kernel<<<1, SAMP_THREADS, 0, st>>>(logits, V, mult, u, R, q_out, tok_out);
+    sample_row_reg_kernel<<<1, SAMP_THREADS, 0, st>>>(logits, V, mult, u, q_out, tok_out);
   } else {
     sample_row_kernel<<<1, SAMP_THREADS, 0, st>>>(logits, V, mult, greedy, u, q_out, tok_out);
   }
@@ -299,6 +332,7 @@ __global__ __launch_bounds__(SAMP_THREADS) void accept_rows_kernel(const float* 
   __shared__ double shd[SAMP_WAVES];
   const int i = blockIdx.x;
   const float* row = logits + (size_t)i * V;
+  const bool reg = V <= SAMP_ROWS_MAX * SAMP_THREADS;   // the row fits the registers of the workgroup
   MaxIdx top;
   float sum = 1.f;
   if (greedy) {
@@ -309,6 +343,9 @@ __global__ __launch_bounds__(SAMP_THREADS) void accept_rows_kernel(const float* 
       m = better(m, t);
     }
     top = block_argmax(m, shm);
+  } else if (reg) {
+    float e[SAMP_ROWS_MAX];
+    reg_softmax(row, V, mult, reg_geom(V), e, top, sum, shm, shd);
   } else {
     row_stats(row, V, mult, shm, shd, top, sum);
   }
@@ -320,7 +357,7 @@ __global__ __launch_bounds__(SAMP_THREADS) void accept_rows_kernel(const float* 
       if (greedy) {
         acc = (x == top.i);
       } else {
-        const float px = expf(row[x] * mult - top.v * mult) / sum;
+        const float px = reg ? reg_prob(row[x], mult, top.v * mult, 1.0f / sum) : expf(row[x] * mult - top.v * mult) / sum;
         acc = ((double)a.r[i] * (double)qrow[x] <= (double)px);
       }
       if (a.force_mask >= 0) acc = (int)((a.force_mask >> i) & 1);
@@ -345,6 +382,7 @@ __global__ __launch_bounds__(SAMP_THREADS) void accept_finish_kernel(const float
                                                                      AcceptResult* __restrict__ res) {
   __shared__ double shd[SAMP_WAVES];
   __shared__ int shi[2];
+  __shared__ double rt[SAMP_WAVES][SAMP_ROWS_MAX + 1];
   int n = 0;
   while (n < a.n_test && __float_as_int(stats[n * 4 + 3]) != 0) ++n;
   const bool rejected = n < a.n_test;
@@ -359,6 +397,32 @@ __global__ __launch_bounds__(SAMP_THREADS) void accept_finish_kernel(const float
       const float* qrow = nullptr;
       if (rejected) qrow = x_direct ? qcache + (size_t)n * V : qcache + (size_t)a.slot[n] * V;
       const float zmax = vmax * mult;
+      if (V <= SAMP_ROWS_MAX * SAMP_THREADS) {
+        // the row in registers: residual weights (or p itself for the bonus / autoregressive token), one draw
+        const RegGeom g = reg_geom(V);
+        const float inv = 1.0f / sum;
+        float e[SAMP_ROWS_MAX];
+#pragma unroll
+        for (int k = 0; k < SAMP_ROWS_MAX; ++k) {
+          const int j = g.j0 + 64 * k;
+          float wj = 0.f;
+          if (k < g.R && j < V) {
+            const float p = reg_prob(row[j], mult, zmax, inv);
+            wj = qrow ? (float)fmax((double)p - (double)qrow[j], 0.0) : p;
+          }
+          e[k] = wj;
+        }
+        double total = 0.0;
+        token = reg_draw(e, g, a.u_resample, rt, shi, &total);
+        if (rejected && !(total > 0.0)) {   // no residual mass in floating point: draw from p itself
+#pragma unroll
+          for (int k = 0; k < SAMP_ROWS_MAX; ++k) {
+            const int j = g.j0 + 64 * k;
+            e[k] = (k < g.R && j < V) ? reg_prob(row[j], mult, zmax, inv) : 0.f;
+          }
+          token = reg_draw(e, g, a.u_resample, rt, shi, nullptr);
+        }
+      } else {
       for (int j = threadIdx.x; j < V; j += SAMP_THREADS) {
         const float p = expf(row[j] * mult - zmax) / sum;
         wbuf[j] = qrow ? (float)fmax((double)p - (double)qrow[j], 0.0) : p;
@@ -373,6 +437,7 @@ __global__ __launch_bounds__(SAMP_THREADS) void accept_finish_kernel(const float
         __threadfence_block();
         __syncthreads();
         token = block_inverse_cdf(wbuf, V, a.u_resample, shd, shi, nullptr);
+      }
       }
     }
   }

@@ -117,7 +117,8 @@ def test_greedy_sampling_is_argmax_with_lowest_id_ties():
     assert tok == 100 and q[100].item() == 1.0 and q.sum().item() == 1.0
 
 
-@pytest.mark.parametrize("V,ls", [(1024, 8.0), (32000, 1.0)])
+# 40000: beyond the register-resident kernels' 32768 ids, the generic path
+@pytest.mark.parametrize("V,ls", [(1024, 8.0), (32000, 1.0), (40000, 1.0)])
 def test_accept_kernel_matches_oracle(V, ls):
     """Rows of target logits against rows of draft distributions: first rejection and the corrected token."""
     amd = _amd()
@@ -156,9 +157,9 @@ def test_accept_kernel_matches_oracle(V, ls):
     assert checked["reject"] >= 1 and checked["reject"] + checked["all"] >= 6, checked
 
 
-def test_accept_kernel_special_cases():
+@pytest.mark.parametrize("V", [2048, 32768, 33008])
+def test_accept_kernel_special_cases(V):
     amd = _amd()
-    V = 2048
     pl = _logit_rows(3, V, 21)
     P = sampling.probs(pl.numpy(), 1.0, 1.0)
     # p == q: always accepted, bonus drawn from the row after the last test
