@@ -5,7 +5,7 @@ import torch
 
 import synth
 from oracle import transformer
-from tests.util import bf16_pair, gpu_available, oracle_model
+from tests.util import NpUniforms, bf16_pair, gpu_available, oracle_model
 
 pytestmark = [pytest.mark.gpu, pytest.mark.skipif(not gpu_available(), reason="needs a GPU")]
 
@@ -204,4 +204,55 @@ def test_graph_replays_equal_kernel_by_kernel_launches():
         outs.append([ctx.draft_step(u, want_token=True) for u in (0.11, 0.52, 0.93, 0.34)])
         ctx.drop_drafts()
     assert outs[0] == outs[1] == outs[2]
+    ctx.close()
+
+
+@pytest.mark.parametrize("case", ["tiny", "gqa64"])
+def test_verify_at_page_and_chunk_boundaries(case):
+    """Context lengths on both sides of the 32-position attention chunks and the 64-token pages, new-token blocks
+    of 1, 7, 17 and 32 rows that start before a boundary and end behind it: the causal mask inside the block, the
+    page-table walk and the K / V append in operand order must hold at every offset."""
+    cfg = CASES[case]()
+    amd, ctx, tm, dm = _setup(cfg, gamma_max=16, extra_seq=512)
+    long_prompt = synth.prompt_tokens(200, cfg.target.vocab, 41).tolist()
+    extra = synth.prompt_tokens(64, cfg.target.vocab, 42).tolist()
+    worst = 0.0
+    for n_prompt in (1, 2, 31, 32, 33, 34, 63, 64, 65, 66, 96, 127, 128, 129, 193):
+        prompt = long_prompt[:n_prompt]
+        ctx.prefill(prompt)
+        ocm = transformer.CachedModel(tm, 512)
+        ocm.feed(prompt[:-1])
+        assert ctx.kv_len(amd.SPEC_TARGET) == n_prompt - 1
+        pos = 0
+        for m in (1, 7, 17, 32):
+            toks = ([prompt[-1]] + extra)[pos:pos + m]
+            pos += m
+            got = ctx.verify(toks, want_logits=True)
+            ref = ocm.feed(toks)
+            err = _rel_err(got, ref)
+            assert err <= LOGIT_TOL, (n_prompt, m, err)
+            worst = max(worst, err)
+    print(f"  boundary sweep {case}: max logit error / range = {worst:.2e}", flush=True)
+    ctx.close()
+
+
+def test_one_token_prompt_then_every_loop():
+    """The shortest prompt: nothing in the caches, the prompt's only token is the frontier.  Greedy AR, SD and PEARL
+    agree from there, and the first target row equals the oracle's."""
+    cfg = CASES["tiny"]()
+    amd, ctx, tm, dm = _setup(cfg, gamma_max=4, temperature=0.0)
+    prompt = [5]
+    uni = NpUniforms(synth.make_uniforms(25, 4, 2))
+    outs = []
+    for algo in (amd.ALGO_AR, amd.ALGO_SD, amd.ALGO_PEARL):
+        ctx.prefill(prompt)
+        assert ctx.kv_len(amd.SPEC_TARGET) == 0 == ctx.kv_len(amd.SPEC_DRAFT)
+        out, st = ctx.generate(algo, 4, 24, uni)
+        outs.append(out)
+    assert outs[0] == outs[1] == outs[2] and len(outs[0]) == 24
+    ctx.prefill(prompt)
+    got = ctx.verify(prompt, want_logits=True)
+    ref = transformer.CachedModel(tm, 8).feed(prompt)
+    assert _rel_err(got, ref) <= LOGIT_TOL
+    assert int(np.argmax(ref[0])) == outs[0][0] or np.sort(ref[0])[-1] - np.sort(ref[0])[-2] < 2e-2 * np.ptp(ref[0])
     ctx.close()
