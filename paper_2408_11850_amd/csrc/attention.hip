@@ -129,34 +129,58 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const bf16* __restrict_
 }
 
 // out[i][head][e] = sum_s w_s O_s[e] / sum_s w_s l_s,  w_s = exp(m_s - max_s m_s).
-// Workgroup = (dh, 4): the four thread rows take every fourth split, then combine through LDS in a fixed order.
+// Workgroup = (dh, 4): the four thread rows take every fourth split and fold them into a running (max, numerator,
+// denominator) triple - no pass for the maximum first, so every load of the kernel is independent of every other
+// and one memory round trip serves them all - then the four triples are combined through LDS in a fixed order.
 #define MERGE_WAYS 4
 __global__ void attn_merge_kernel(const float* __restrict__ opart, const float* __restrict__ mlpart,
                                   bf16* __restrict__ out, int M, int Hq, int Hkv, int dh, int nsplit, int Rpad) {
   __shared__ float sm[MERGE_WAYS], snum[MERGE_WAYS][128], sden[MERGE_WAYS];
   const int i = blockIdx.x, head = blockIdx.y, e = threadIdx.x, y = threadIdx.y;
   const int G = Hq / Hkv, kvh = head / G, Rr = i * G + head % G;
-  float mloc = NEG_BIG;
-  for (int s = y; s < nsplit; s += MERGE_WAYS) mloc = fmaxf(mloc, mlpart[(((size_t)s * Hkv + kvh) * Rpad + Rr) * 2]);
-  if (e == 0) sm[y] = mloc;
-  __syncthreads();
-  float mstar = sm[0];
+  float mrun = NEG_BIG, num = 0.f, den = 0.f;
+  int s = y;
+  for (; s + 3 * MERGE_WAYS < nsplit; s += 4 * MERGE_WAYS) {   // four splits' loads in flight
+    float ms[4], ls[4], os[4];
 #pragma unroll
-  for (int k = 1; k < MERGE_WAYS; ++k) mstar = fmaxf(mstar, sm[k]);
-  float num = 0.f, den = 0.f;
-  for (int s = y; s < nsplit; s += MERGE_WAYS) {
+    for (int k = 0; k < 4; ++k) {
+      const size_t row = ((size_t)(s + k * MERGE_WAYS) * Hkv + kvh) * Rpad + Rr;
+      ms[k] = mlpart[row * 2];
+      ls[k] = mlpart[row * 2 + 1];
+      os[k] = opart[row * dh + e];
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const float mnew = fmaxf(mrun, ms[k]);
+      const float c0 = __expf(mrun - mnew), c1 = __expf(ms[k] - mnew);
+      num = num * c0 + c1 * os[k];
+      den = den * c0 + c1 * ls[k];
+      mrun = mnew;
+    }
+  }
+  for (; s < nsplit; s += MERGE_WAYS) {
     const size_t row = ((size_t)s * Hkv + kvh) * Rpad + Rr;
-    const float wgt = __expf(mlpart[row * 2] - mstar);
-    den += wgt * mlpart[row * 2 + 1];
-    num += wgt * opart[row * dh + e];
+    const float m1 = mlpart[row * 2], l1 = mlpart[row * 2 + 1], o1 = opart[row * dh + e];
+    const float mnew = fmaxf(mrun, m1);
+    const float c0 = __expf(mrun - mnew), c1 = __expf(m1 - mnew);
+    num = num * c0 + c1 * o1;
+    den = den * c0 + c1 * l1;
+    mrun = mnew;
   }
   snum[y][e] = num;
-  if (e == 0) sden[y] = den;
+  if (e == 0) sm[y] = mrun, sden[y] = den;
   __syncthreads();
   if (y == 0) {
-    float n = snum[0][e], dd = sden[0];
+    float mstar = sm[0];
 #pragma unroll
-    for (int k = 1; k < MERGE_WAYS; ++k) n += snum[k][e], dd += sden[k];
+    for (int k = 1; k < MERGE_WAYS; ++k) mstar = fmaxf(mstar, sm[k]);
+    float n = 0.f, dd = 0.f;
+#pragma unroll
+    for (int k = 0; k < MERGE_WAYS; ++k) {
+      const float c = __expf(sm[k] - mstar);    // a thread row that took no split holds (NEG_BIG, 0, 0): weight 0 or 0 * 1
+      n += c * snum[k][e];
+      dd += c * sden[k];
+    }
     out[((size_t)i * Hq + head) * dh + e] = __float2bfloat16(n / dd);
   }
 }
