@@ -256,3 +256,32 @@ def test_one_token_prompt_then_every_loop():
     assert _rel_err(got, ref) <= LOGIT_TOL
     assert int(np.argmax(ref[0])) == outs[0][0] or np.sort(ref[0])[-1] - np.sort(ref[0])[-2] < 2e-2 * np.ptp(ref[0])
     ctx.close()
+
+
+@pytest.mark.parametrize("prefill_mode", [1, 0], ids=["dense_prefill", "chunked_prefill"])
+def test_benchmark_context_length_matches_oracle(prefill_mode):
+    """The context length the benchmark runs at (4096-token prompt: 64 pages, the largest K/V split counts, one
+    full block of the matrix-core prompt pass or 128 verify-sized forwards) on a narrow GQA model with head_dim 128
+    that the fp64 oracle can follow: rows of 1, 7 and 8 new tokens against the oracle."""
+    cfg = CASES["gqa128"]()
+    cfg.n_prompt, cfg.n_generate = 4096, 64
+    amd, ctx, tm, dm = _setup(cfg, gamma_max=8)
+    ctx.set_option(amd.SPEC_OPT_PREFILL, prefill_mode)
+    prompt = synth.prompt_tokens(cfg.n_prompt, cfg.target.vocab, 51).tolist()
+    extra = synth.prompt_tokens(16, cfg.target.vocab, 52).tolist()
+    ctx.prefill(prompt)
+    assert ctx.kv_len(amd.SPEC_TARGET) == 4095
+    print("oracle prompt pass over 4095 tokens", flush=True)
+    ocm = transformer.CachedModel(tm, 4096 + 32)
+    for b in range(0, 4095, 512):                      # blocks keep the oracle's score matrices small
+        ocm.feed(prompt[b:min(b + 512, 4095)])
+    worst, pos = 0.0, 0
+    for m in (1, 7, 8):
+        toks = ([prompt[-1]] + extra)[pos:pos + m]
+        pos += m
+        got = ctx.verify(toks, want_logits=True)
+        ref = ocm.feed(toks)
+        worst = max(worst, _rel_err(got, ref))
+        print(f"  M={m}: logit error / range so far {worst:.2e}", flush=True)
+    assert worst <= LOGIT_TOL
+    ctx.close()
