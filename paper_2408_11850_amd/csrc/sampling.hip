@@ -5,7 +5,9 @@
 // one-hot at the arg-max (lowest id on ties) for greedy decoding.  A draw is an inverse-CDF walk in
 // ascending token id with one uniform u: the first k whose running sum (fp64) exceeds u * total.
 // The acceptance test is evaluated without a division, in fp64: accept iff r * q[x] <= p[x].
-// One workgroup of 1024 threads handles one vocabulary row; these kernels are latency-bound.
+// One workgroup of 1024 threads handles one vocabulary row.  With a single compute unit per row the kernels are
+// bound by its vector ALU and by the latency of dependent passes, so rows of up to 32768 ids are held in
+// registers and read once (the reg_* functions); longer rows take the generic multi-pass kernels.
 #include "spec_internal.h"
 
 #define SAMP_THREADS 1024
