@@ -55,8 +55,8 @@ struct ModelRt {
   float *partials = nullptr, *opart = nullptr, *mlpart = nullptr, *logits = nullptr;
   long long n_forwards = 0;
   int split_tokens = 0;           // context length the attention split count is sized for (fixed per context)
-  // captured forwards, keyed [tokens][logit mode 0/1/2][projection workgroups per CU]
-  hipGraphExec_t graphs[SPEC_MAX_TOKENS + 1][3][3] = {};
+  // captured forwards, keyed [tokens][logit mode 0/1/2][projection workgroups per CU][first layers / the rest]
+  hipGraphExec_t graphs[SPEC_MAX_TOKENS + 1][3][3][2] = {};
   // activation buffers of the dense prompt path, allocated at its first use for pf_cap tokens
   int pf_cap = 0;
   int* pf_tok = nullptr;
@@ -182,11 +182,12 @@ int init_model(ModelRt& m, const spec_model_desc& d, const spec_weights& w, cons
 void free_model(ModelRt& m) {
   for (auto& a : m.graphs)
     for (auto& b : a)
-      for (hipGraphExec_t& g : b)
-        if (g) {
-          (void)hipGraphExecDestroy(g);
-          g = nullptr;
-        }
+      for (auto& cc : b)
+        for (hipGraphExec_t& g : cc)
+          if (g) {
+            (void)hipGraphExecDestroy(g);
+            g = nullptr;
+          }
   void* ptrs[] = {m.pool, m.block_table_dev, m.len_dev, m.tok_in, m.h, m.ssq, m.a, m.qbuf, m.attn_out, m.z, m.partials,
                   m.opart, m.logits, m.pf_tok, m.pf_h, m.pf_a, m.pf_q, m.pf_attn, m.pf_z, m.pf_rope};
   for (void* p : ptrs)
@@ -252,22 +253,24 @@ int run_gemm(spec_ctx* c, int which, ModelRt& m, int M, int N, int K, const bf16
 // The kernel chain of one forward over the M tokens in m.tok_in.  Nothing here depends on host state other
 // than M, logit_rows and the launch mode: positions come from *len_dev, pages from the device block table,
 // so the chain can be captured once into a HIP graph and replayed.
-int enqueue_forward(spec_ctx* c, int which, int M, int logit_rows) {
+// Layers [l0, l1) of the chain: the embedding goes with layer 0, the LM head and the length update with the last layer.
+int enqueue_forward(spec_ctx* c, int which, int M, int logit_rows, int l0, int l1) {
   ModelRt& m = c->m[which];
   const spec_model_desc& d = m.d;
   hipStream_t st = m.stream;
   int rc;
-  HIPCHK(launch_embed(m.h, (const bf16*)m.tok_embed, m.tok_in, M, d.d_model, d.vocab, st));
+  if (l0 == 0) HIPCHK(launch_embed(m.h, (const bf16*)m.tok_embed, m.tok_in, M, d.d_model, d.vocab, st));
   const int qkvN = (d.n_heads + 2 * d.n_kv_heads) * d.head_dim;
   const int HD = d.n_heads * d.head_dim;
   GemmPlan p;
-  const float* prev = nullptr;
-  int prevS = 0;
+  // a chain that starts behind layer 0 first adds the K slices the previous layer's down projection left
+  const float* prev = l0 > 0 ? m.partials : nullptr;
+  int prevS = l0 > 0 ? gemm_plan(M, d.d_model, d.d_ffn, c->wgs).S : 0;
   // Every RMSNorm is split in three: a residual add spread over several workgroups per row, which leaves the
   // rows' sums of squares and x' = bf16(h * gain); the projection of x'; and the factor 1/rms, applied to the
   // projection's output rows by the kernel that adds its K slices.
   RowScale rs{m.ssq, 0, d.d_model, d.rms_eps};
-  for (int l = 0; l < d.n_layers; ++l) {
+  for (int l = l0; l < l1; ++l) {
     HIPCHK(launch_add_sumsq(m.h, prev, prevS, (const bf16*)m.attn_norm[l], m.a, m.ssq, M, d.d_model, &rs.W, st));
     if ((rc = run_gemm(c, which, m, M, qkvN, d.d_model, m.a, m.wqkv[l], &p))) return rc;
     HIPCHK(launch_rope_append(m.partials, p.S, m.qbuf, m.pool, m.block_table_dev, m.len_dev, m.geom, l, M, d.n_heads,
@@ -282,6 +285,7 @@ int enqueue_forward(spec_ctx* c, int which, int M, int logit_rows) {
     prev = m.partials;
     prevS = p.S;
   }
+  if (l1 < d.n_layers) return SPEC_OK;
   if (logit_rows > 0) {
     HIPCHK(launch_add_sumsq(m.h, prev, prevS, (const bf16*)m.final_norm, m.a, m.ssq, M, d.d_model, &rs.W, st));
     const int rows = logit_rows >= M ? M : 1;
@@ -304,28 +308,35 @@ int forward(spec_ctx* c, int which, const TokenSrc& src, int logit_rows) {
   if ((rc = ensure_pages(m, m.len + M))) return rc;
   hipStream_t st = m.stream;
   HIPCHK(launch_gather_tokens(m.tok_in, c->ring, src, st));
+  const int L = m.d.n_layers;
   if (c->use_graphs && !(c->profile_flags & 1)) {
     const int lm = logit_rows == 0 ? 0 : (logit_rows >= M ? 2 : 1);
-    hipGraphExec_t& ge = m.graphs[M][lm][c->wgs];
-    if (!ge) {
-      HIPCHK(hipStreamBeginCapture(st, hipStreamCaptureModeRelaxed));
-      rc = enqueue_forward(c, which, M, logit_rows);
-      hipGraph_t g = nullptr;
-      hipError_t e = hipStreamEndCapture(st, &g);   // always leave capture mode, also after a failed launch
-      if (rc || e != hipSuccess) {
-        if (g) (void)hipGraphDestroy(g);
-        if (!rc) FAIL(SPEC_E_HIP, "hipStreamEndCapture failed: %s", hipGetErrorString(e));
-        return rc;
+    // Two graphs per forward: launching ~10 nodes per layer costs the host about 0.45 us per node (0.45 ms for the
+    // 80-layer target), during which the stream would sit idle; a short graph of the first layers is on the GPU in
+    // tens of microseconds and runs while the host launches the rest.
+    const int Lh = L >= 8 ? 4 : L;
+    for (int part = 0; part < (Lh < L ? 2 : 1); ++part) {
+      hipGraphExec_t& ge = m.graphs[M][lm][c->wgs][part];
+      if (!ge) {
+        HIPCHK(hipStreamBeginCapture(st, hipStreamCaptureModeRelaxed));
+        rc = enqueue_forward(c, which, M, logit_rows, part ? Lh : 0, part ? L : Lh);
+        hipGraph_t g = nullptr;
+        hipError_t e = hipStreamEndCapture(st, &g);   // always leave capture mode, also after a failed launch
+        if (rc || e != hipSuccess) {
+          if (g) (void)hipGraphDestroy(g);
+          if (!rc) FAIL(SPEC_E_HIP, "hipStreamEndCapture failed: %s", hipGetErrorString(e));
+          return rc;
+        }
+        e = hipGraphInstantiate(&ge, g, nullptr, nullptr, 0);
+        (void)hipGraphDestroy(g);
+        if (e != hipSuccess) {
+          ge = nullptr;
+          FAIL(SPEC_E_HIP, "hipGraphInstantiate failed: %s", hipGetErrorString(e));
+        }
       }
-      e = hipGraphInstantiate(&ge, g, nullptr, nullptr, 0);
-      (void)hipGraphDestroy(g);
-      if (e != hipSuccess) {
-        ge = nullptr;
-        FAIL(SPEC_E_HIP, "hipGraphInstantiate failed: %s", hipGetErrorString(e));
-      }
+      HIPCHK(hipGraphLaunch(ge, st));
     }
-    HIPCHK(hipGraphLaunch(ge, st));
-  } else if ((rc = enqueue_forward(c, which, M, logit_rows))) {
+  } else if ((rc = enqueue_forward(c, which, M, logit_rows, 0, L))) {
     return rc;
   }
   m.len += M;
