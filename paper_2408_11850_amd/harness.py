@@ -107,6 +107,8 @@ def calibrate_gamma(ctx: SpecContext, n_iter: int = 8, cap: int = 16) -> Tuple[i
     """Window size gamma = round(c), c = T(target forward) / T(draft forward) (paper Section 4.4.1),
     both timed alone at the current context length.  Leaves the caches as it found them."""
     lt, ld = ctx.kv_len(SPEC_TARGET), ctx.kv_len(SPEC_DRAFT)
+    ctx.verify([0])                      # untimed: the first forward of a shape also captures its graphs
+    ctx.rollback_kv(SPEC_TARGET, lt)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(n_iter):
@@ -114,6 +116,10 @@ def calibrate_gamma(ctx: SpecContext, n_iter: int = 8, cap: int = 16) -> Tuple[i
     torch.cuda.synchronize()
     tp = (time.perf_counter() - t0) / n_iter
     ctx.rollback_kv(SPEC_TARGET, lt)
+    ctx.draft_step(0.5)
+    ctx.drop_drafts()
+    ctx.rollback_kv(SPEC_DRAFT, ld)
+    torch.cuda.synchronize()
     t0 = time.perf_counter()
     n_d = min(n_iter, 2 * ctx.gamma_max)
     for _ in range(n_d):
