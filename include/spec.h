@@ -115,11 +115,14 @@ int spec_prefill(spec_ctx* ctx, const int32_t* prompt_host, int n_prompt, int wh
 int spec_draft_step(spec_ctx* ctx, float u, int32_t* tok_out_host);
 
 /* One target forward over n_tokens tokens against the KV cache, asynchronous on the target
- * stream ("the target model verifies these draft tokens in parallel within a single forward",
- * Section 1; rows p_1..p_n of Section 2).  tokens_host == NULL selects the tokens the step
- * needs: the frontier followed by the first n_tokens-1 unverified drafts (these are read on
- * the device; the target stream waits for the draft stream first).  If logits_out_host is not
- * NULL the call synchronises and copies the fp32 logits [n_tokens][vocab] (tests only). */
+ * stream: the verification of several draft tokens in one forward (Section 1; rows p_1..p_n
+ * of Section 2).  tokens_host == NULL selects the tokens the step needs: the frontier followed
+ * by the first n_tokens-1 unverified drafts, read on the device.  If one of those drafts is
+ * still being produced (vanilla SD verifies the chain it has just launched; PEARL's rows were
+ * drafted in earlier steps) the call blocks the host until the draft stream has produced it and
+ * only then enqueues the forward: a target stream parked on a device-side wait slows the draft
+ * stream's kernel launches.  If logits_out_host is not NULL the call synchronises and copies the
+ * fp32 logits [n_tokens][vocab] (tests only). */
 int spec_verify(spec_ctx* ctx, const int32_t* tokens_host, int n_tokens, float* logits_out_host);
 
 /* Speculative-sampling accept / reject on the device (Eq. (1): accept x iff r <= p[x]/q[x];
