@@ -218,3 +218,23 @@ def test_figure3_trace_on_gpu():
         else:
             break
     ctx.close()
+
+
+def test_gamma_calibration_leaves_the_state_as_it_found_it():
+    """gamma = round(T_target / T_draft) (Section 4.4.1) is measured with real forwards on both models; afterwards
+    the caches, the pending drafts and the next tokens must be what they were."""
+    cfg = synth.config("tiny")
+    amd, harness, target, draft, tm, dm = _pair(cfg)
+    prompt = synth.prompt_tokens(cfg.n_prompt, cfg.target.vocab, 13).tolist()
+    uni = NpUniforms(synth.make_uniforms(17, 4, 8))
+    ctx = harness.make_context(cfg, target, draft, 8)
+    ctx.prefill(prompt)
+    ref, _ = ctx.generate(amd.ALGO_PEARL, 4, 16, uni)
+    ctx.prefill(prompt)
+    lens = (ctx.kv_len(amd.SPEC_TARGET), ctx.kv_len(amd.SPEC_DRAFT), ctx.committed_len())
+    g, tp, tq = harness.calibrate_gamma(ctx, n_iter=3, cap=8)
+    assert 1 <= g <= 8 and tp > 0 and tq > 0 and g == max(1, min(8, int(round(tp / tq))))
+    assert (ctx.kv_len(amd.SPEC_TARGET), ctx.kv_len(amd.SPEC_DRAFT), ctx.committed_len()) == lens
+    out, _ = ctx.generate(amd.ALGO_PEARL, 4, 16, uni)
+    assert out == ref
+    ctx.close()
