@@ -8,8 +8,8 @@
 // A wave therefore reads its share of a panel as consecutive fully-coalesced 1 KiB loads.
 //
 // Work split: the K axis is cut into S slices; a workgroup of 8 waves owns one slice and a
-// contiguous range of panels; wave w owns `spw` consecutive steps of the slice and keeps the
-// matching activation fragments (the B operand) in registers for the whole kernel.  After every
+// contiguous range of panels; the slice's steps are dealt evenly to its 8 waves (at most 8 consecutive steps
+// each), and a wave keeps the matching activation fragments (the B operand) in registers for the whole kernel.  After every
 // round of 4 panels the 8 wave-partials are summed through LDS in a fixed order and written to
 // P[s][m][n] (fp32).  Consumers add the S slices in ascending order, so results do not depend
 // on timing.
@@ -34,11 +34,26 @@ GemmPlan gemm_plan(int M, int N, int K, int wgs_per_cu) {
   if (wgs_per_cu > 2) wgs_per_cu = 2;
   const int slots = SPEC_NUM_CU * wgs_per_cu;
   const int spwmax = 8;
-  p.S = (p.steps + GEMM_WAVES * spwmax - 1) / (GEMM_WAVES * spwmax);
-  // small matrices: cut K finer until every workgroup slot (at two per CU) has work.  The K split depends
-  // on the shape only, never on wgs_per_cu, so both launch modes add the same numbers in the same order.
+  // The K split depends on the shape only, never on wgs_per_cu (always planned for two workgroups per CU), so both
+  // launch modes add the same numbers in the same order.  The fewest slices a wave's 8 steps allow are not always
+  // the best: K = 28672 gives 14 slices, 36 groups of workgroups for 512 panels and a tail of groups with 15
+  // panels instead of 14.2; 16 slices of 7 steps give 32 groups of 16 panels.  Among S .. 2 S slices (at least 4
+  // steps per wave) the split with the least work for the busiest wave is taken: panels per group x steps per wave.
+  const int smin = (p.steps + GEMM_WAVES * spwmax - 1) / (GEMM_WAVES * spwmax);
+  long long best = -1;
+  p.S = smin;
+  for (int S = smin; S <= 2 * smin; ++S) {
+    const int spw = (p.steps + GEMM_WAVES * S - 1) / (GEMM_WAVES * S);
+    if (S > smin && spw < 4) break;
+    int Gs = 2 * SPEC_NUM_CU / S;
+    if (Gs < 1) Gs = 1;
+    if (Gs > p.NT) Gs = p.NT;
+    const long long cost = (long long)((p.NT + Gs - 1) / Gs) * spw;
+    if (best < 0 || cost < best) best = cost, p.S = S;
+  }
+  // small matrices: cut K finer until every workgroup slot (at two per CU) has work
   while (p.S * p.NT < 2 * SPEC_NUM_CU && (p.steps + GEMM_WAVES * p.S * 2 - 1) / (GEMM_WAVES * p.S * 2) >= 2) p.S *= 2;
-  p.spw = (p.steps + GEMM_WAVES * p.S - 1) / (GEMM_WAVES * p.S);
+  p.spw = (p.steps + GEMM_WAVES * p.S - 1) / (GEMM_WAVES * p.S);   // most steps a wave takes
   p.Gs = slots / p.S;
   if (p.Gs < 1) p.Gs = 1;
   if (p.Gs > p.NT) p.Gs = p.NT;
@@ -85,10 +100,10 @@ __global__ __launch_bounds__(GEMM_THREADS, WPE) void gemm_partial_kernel(const b
   const int p1 = (int)((long long)(idx + 1) * NT / Gs);
   const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int c = lane & 15, kb = lane >> 4;
-  const int step0 = (s * GEMM_WAVES + w) * spw;
-  int nst = steps - step0;
-  if (nst > spw) nst = spw;
-  if (nst < 0) nst = 0;
+  // the K steps are dealt evenly to the S * 8 waves that share a panel: floor / ceil of steps / (8 S) each
+  const int ws = s * GEMM_WAVES + w, nws = S * GEMM_WAVES;
+  const int step0 = (int)((long long)ws * steps / nws);
+  const int nst = (int)((long long)(ws + 1) * steps / nws) - step0;   // <= spw <= SPWMAX
 
   // activation fragments of this wave's K range, kept for the whole kernel
   bf16x8 b[MT][SPWMAX];
@@ -179,9 +194,23 @@ __global__ void reduce_partials_kernel(float* __restrict__ y, const float* __res
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= n4) return;
   const f32x4* p = reinterpret_cast<const f32x4*>(P);
-  f32x4 t = p[i];
-  for (int s = 1; s < S; ++s) t += p[(size_t)s * n4 + i];
-  if (rs.ssq) t *= rs.inv((int)(i / (size_t)N4));
+  // slices in groups of four independent loads, added in ascending order
+  f32x4 v[4];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) v[k] = (k < S) ? p[(size_t)k * n4 + i] : f32x4{0.f, 0.f, 0.f, 0.f};
+  const float inv = rs.ssq ? rs.inv((int)(i / (size_t)N4)) : 1.0f;
+  f32x4 t = v[0];
+#pragma unroll
+  for (int k = 1; k < 4; ++k)
+    if (k < S) t += v[k];
+  for (int s0 = 4; s0 < S; s0 += 4) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) v[k] = (s0 + k < S) ? p[(size_t)(s0 + k) * n4 + i] : f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+      if (s0 + k < S) t += v[k];
+  }
+  if (rs.ssq) t *= inv;
   reinterpret_cast<f32x4*>(y)[i] = t;
 }
 

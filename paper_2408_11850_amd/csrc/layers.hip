@@ -163,7 +163,7 @@ __global__ __launch_bounds__(ADDSQ_THREADS) void add_sumsq_kernel(float* __restr
     float tot = 0.f;
 #pragma unroll
     for (int k = 0; k < ADDSQ_THREADS / 64; ++k) tot += sh[k];
-    ssq[m * W + w] = tot;
+    ssq[m * ADDSQ_MAX_PIECES + w] = tot;
   }
 }
 hipError_t launch_add_sumsq(float* h, const float* partials, int S, const bf16* gain, bf16* a, float* ssq, int M,
@@ -203,17 +203,20 @@ __global__ void rope_append_kernel(const float* __restrict__ P, int S, bf16* __r
   const int e = threadIdx.x & 63;
   if (e >= half || head >= Hq + 2 * Hkv) return;
   const int pos = len_ptr[0] + i;
-  float x0 = 0.f, x1 = 0.f;
-  for (int s = 0; s < S; ++s) {
-    const float* row = P + ((size_t)s * M + i) * N + (size_t)head * dh;
-    x0 += row[e];
-    x1 += row[e + half];
+  // The kernel is one chain of latencies, so every load goes out before anything waits: the first four K slices,
+  // the row's sums of squares, the position; the fp64 angle is worked out while they are in flight.  Slices are
+  // added in ascending order whatever the grouping.
+  const float* base = P + (size_t)i * N + (size_t)head * dh;
+  const size_t sstride = (size_t)M * N;
+  float a0[4], a1[4];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    a0[k] = (k < S) ? base[k * sstride + e] : 0.f;
+    a1[k] = (k < S) ? base[k * sstride + e + half] : 0.f;
   }
   const float inv = rs.inv(i);
-  x0 *= inv;
-  x1 *= inv;
-  if (head < Hq + Hkv) {   // rotate pair (e, e + dh/2) by pos * theta^(-2e/dh)
-    float cs, sn;
+  float cs = 1.f, sn = 0.f;
+  if (head < Hq + Hkv) {   // rotation of pair (e, e + dh/2) by pos * theta^(-2e/dh)
     if (tab) {
       const float2 t = tab[(size_t)i * half + e];
       cs = t.x; sn = t.y;
@@ -221,6 +224,24 @@ __global__ void rope_append_kernel(const float* __restrict__ P, int S, bf16* __r
       const double ang = (double)pos * pow((double)theta, -2.0 * (double)e / (double)dh);
       cs = (float)cos(ang); sn = (float)sin(ang);
     }
+  }
+  float x0 = 0.f, x1 = 0.f;
+#pragma unroll
+  for (int k = 0; k < 4; ++k)
+    if (k < S) { x0 += a0[k]; x1 += a1[k]; }
+  for (int s0 = 4; s0 < S; s0 += 4) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      a0[k] = (s0 + k < S) ? base[(s0 + k) * sstride + e] : 0.f;
+      a1[k] = (s0 + k < S) ? base[(s0 + k) * sstride + e + half] : 0.f;
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+      if (s0 + k < S) { x0 += a0[k]; x1 += a1[k]; }
+  }
+  x0 *= inv;
+  x1 *= inv;
+  if (head < Hq + Hkv) {
     const float y0 = x0 * cs - x1 * sn, y1 = x0 * sn + x1 * cs;
     x0 = y0; x1 = y1;
   }
@@ -263,13 +284,31 @@ __global__ void silu_mul_kernel(const float* __restrict__ P, int S, bf16* __rest
   const int f = blockIdx.x * blockDim.x + threadIdx.x;
   if (f >= F) return;
   const int gc = (f >> 4) * 32 + (f & 15);
-  float gv = 0.f, uv = 0.f;
-  for (int s = 0; s < S; ++s) {
-    const float* row = P + ((size_t)s * M + m) * (2 * (size_t)F);
-    gv += row[gc];
-    uv += row[gc + 16];
+  // all loads of the first four K slices and of the row's sums of squares go out together (one round trip);
+  // slices are added in ascending order whatever the grouping
+  const float* base = P + (size_t)m * (2 * (size_t)F) + gc;
+  const size_t sstride = (size_t)M * (2 * (size_t)F);
+  float g4[4], u4[4];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    g4[k] = (k < S) ? base[k * sstride] : 0.f;
+    u4[k] = (k < S) ? base[k * sstride + 16] : 0.f;
   }
   const float inv = rs.inv(m);
+  float gv = 0.f, uv = 0.f;
+#pragma unroll
+  for (int k = 0; k < 4; ++k)
+    if (k < S) { gv += g4[k]; uv += u4[k]; }
+  for (int s0 = 4; s0 < S; s0 += 4) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      g4[k] = (s0 + k < S) ? base[(s0 + k) * sstride] : 0.f;
+      u4[k] = (s0 + k < S) ? base[(s0 + k) * sstride + 16] : 0.f;
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+      if (s0 + k < S) { gv += g4[k]; uv += u4[k]; }
+  }
   gv *= inv;
   uv *= inv;
   const float sg = gv / (1.0f + __expf(-gv));

@@ -159,6 +159,7 @@ int init_model(ModelRt& m, const spec_model_desc& d, const spec_weights& w, cons
   if ((rc = dev_alloc(&m.tok_in, (size_t)MX))) return rc;
   if ((rc = dev_alloc(&m.h, (size_t)MX * d.d_model))) return rc;
   if ((rc = dev_alloc(&m.ssq, (size_t)MX * ADDSQ_MAX_PIECES))) return rc;
+  HIPCHK(hipMemset(m.ssq, 0, (size_t)MX * ADDSQ_MAX_PIECES * sizeof(float)));
   if ((rc = dev_alloc(&m.a, (size_t)MX * amax))) return rc;
   if ((rc = dev_alloc(&m.qbuf, (size_t)MX * d.n_heads * d.head_dim))) return rc;
   if ((rc = dev_alloc(&m.attn_out, (size_t)MX * d.n_heads * d.head_dim))) return rc;
@@ -292,7 +293,7 @@ int enqueue_forward(spec_ctx* c, int which, int M, int logit_rows, int l0, int l
     const bf16* x = m.a + (size_t)(M - rows) * d.d_model;
     if ((rc = run_gemm(c, which, m, rows, d.vocab, d.d_model, x, m.lm_head, &p))) return rc;
     RowScale rl = rs;
-    rl.ssq = m.ssq + (size_t)(M - rows) * rs.W;
+    rl.ssq = m.ssq + (size_t)(M - rows) * ADDSQ_MAX_PIECES;
     HIPCHK(launch_reduce_partials(m.logits, m.partials, p.S, (size_t)rows * d.vocab, st, rl, d.vocab));
   }
   HIPCHK(launch_add_int(m.len_dev, M, st));

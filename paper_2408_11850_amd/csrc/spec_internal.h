@@ -43,14 +43,23 @@ hipError_t launch_gemm_partials(const GemmPlan& p, const bf16* x, const void* wp
 // slices multiplies the sum by inv_m = 1 / sqrt(sum_w ssq[m][w] / d + eps) (the projection is linear in its rows
 // and bf16 keeps the same relative precision at any scale).  ssq == nullptr: no scaling.
 struct RowScale {
-  const float* ssq;    // [rows][W]
+  const float* ssq;    // [rows][ADDSQ_MAX_PIECES], pieces beyond W are zero
   int W, d;
   float eps;
 #ifdef __HIPCC__
+  // the row's pieces come in up to four independent 16-byte loads (one round trip) and are added in ascending order
   __device__ __forceinline__ float inv(int m) const {
     if (!ssq) return 1.0f;
+    const f32x4* p = reinterpret_cast<const f32x4*>(ssq + (size_t)m * 16);
+    const int nv = (W + 3) >> 2;
+    f32x4 v[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) v[k] = (k < nv) ? p[k] : f32x4{0.f, 0.f, 0.f, 0.f};
     float tot = 0.f;
-    for (int i = 0; i < W; ++i) tot += ssq[m * W + i];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      tot += v[k].x; tot += v[k].y; tot += v[k].z; tot += v[k].w;
+    }
     return 1.0f / sqrtf(tot / (float)d + eps);
   }
 #endif
@@ -94,8 +103,10 @@ hipError_t launch_embed(float* h, const bf16* embed, const int* tok, int M, int 
 hipError_t launch_addnorm(float* h, const float* partials, int S, const bf16* gain, bf16* a, int M, int d,
                           float eps, hipStream_t st);
 // h += sum_s partials[s] (if partials), a = bf16(h * gain) (not normalised), ssq[m][w] = sum of h^2 over the w-th
-// piece of 1024 columns of row m; returns the number of pieces W through *W_out (ssq needs M * W floats)
+// piece of 1024 columns of row m (row stride ADDSQ_MAX_PIECES; the caller zeroes the buffer once, pieces beyond W
+// are never written); returns the number of pieces W through *W_out
 #define ADDSQ_MAX_PIECES 16
+static_assert(ADDSQ_MAX_PIECES == 16, "RowScale::inv reads a row of sums of squares as four 16-byte vectors");
 hipError_t launch_add_sumsq(float* h, const float* partials, int S, const bf16* gain, bf16* a, float* ssq, int M,
                             int d, int* W_out, hipStream_t st);
 // tab: optional [M][dh/2] (cos, sin) table from launch_rope_table for the same len; nullptr = compute in place
