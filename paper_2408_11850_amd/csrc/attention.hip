@@ -129,43 +129,38 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const bf16* __restrict_
 }
 
 // out[i][head][e] = sum_s w_s O_s[e] / sum_s w_s l_s,  w_s = exp(m_s - max_s m_s).
-// Workgroup = (dh, 4): the four thread rows take every fourth split and fold them into a running (max, numerator,
-// denominator) triple - no pass for the maximum first, so every load of the kernel is independent of every other
-// and one memory round trip serves them all - then the four triples are combined through LDS in a fixed order.
-#define MERGE_WAYS 4
-__global__ void attn_merge_kernel(const float* __restrict__ opart, const float* __restrict__ mlpart,
-                                  bf16* __restrict__ out, int M, int Hq, int Hkv, int dh, int nsplit, int Rpad) {
+// Workgroup = (dh, 8): the eight thread rows take every eighth split and fold them into a running (max, numerator,
+// denominator) triple - no pass for the maximum first, and eight splits' loads in flight per thread, so up to 64
+// splits cost one memory round trip - then the eight triples are combined through LDS in a fixed order.
+#define MERGE_WAYS 8
+#define MERGE_UNROLL 8
+__global__ __launch_bounds__(128 * MERGE_WAYS) void attn_merge_kernel(const float* __restrict__ opart,
+                                                                      const float* __restrict__ mlpart,
+                                                                      bf16* __restrict__ out, int M, int Hq, int Hkv,
+                                                                      int dh, int nsplit, int Rpad) {
   __shared__ float sm[MERGE_WAYS], snum[MERGE_WAYS][128], sden[MERGE_WAYS];
   const int i = blockIdx.x, head = blockIdx.y, e = threadIdx.x, y = threadIdx.y;
   const int G = Hq / Hkv, kvh = head / G, Rr = i * G + head % G;
   float mrun = NEG_BIG, num = 0.f, den = 0.f;
-  int s = y;
-  for (; s + 3 * MERGE_WAYS < nsplit; s += 4 * MERGE_WAYS) {   // four splits' loads in flight
-    float ms[4], ls[4], os[4];
+  for (int s = y; s < nsplit; s += MERGE_UNROLL * MERGE_WAYS) {
+    float ms[MERGE_UNROLL], ls[MERGE_UNROLL], os[MERGE_UNROLL];
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      const size_t row = ((size_t)(s + k * MERGE_WAYS) * Hkv + kvh) * Rpad + Rr;
-      ms[k] = mlpart[row * 2];
-      ls[k] = mlpart[row * 2 + 1];
-      os[k] = opart[row * dh + e];
+    for (int k = 0; k < MERGE_UNROLL; ++k) {
+      const int sk = s + k * MERGE_WAYS;
+      const size_t row = ((size_t)(sk < nsplit ? sk : s) * Hkv + kvh) * Rpad + Rr;
+      const bool in = sk < nsplit;
+      ms[k] = in ? mlpart[row * 2] : NEG_BIG;
+      ls[k] = in ? mlpart[row * 2 + 1] : 0.f;
+      os[k] = in ? opart[row * dh + e] : 0.f;
     }
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
+    for (int k = 0; k < MERGE_UNROLL; ++k) {
       const float mnew = fmaxf(mrun, ms[k]);
       const float c0 = __expf(mrun - mnew), c1 = __expf(ms[k] - mnew);
       num = num * c0 + c1 * os[k];
       den = den * c0 + c1 * ls[k];
       mrun = mnew;
     }
-  }
-  for (; s < nsplit; s += MERGE_WAYS) {
-    const size_t row = ((size_t)s * Hkv + kvh) * Rpad + Rr;
-    const float m1 = mlpart[row * 2], l1 = mlpart[row * 2 + 1], o1 = opart[row * dh + e];
-    const float mnew = fmaxf(mrun, m1);
-    const float c0 = __expf(mrun - mnew), c1 = __expf(m1 - mnew);
-    num = num * c0 + c1 * o1;
-    den = den * c0 + c1 * l1;
-    mrun = mnew;
   }
   snum[y][e] = num;
   if (e == 0) sm[y] = mrun, sden[y] = den;
