@@ -192,6 +192,11 @@ size_t spec_packed_bytes(int N, int K);
 int spec_gemm(float* y_dev, const void* x_dev, const void* w_packed_dev, int M, int N, int K,
               void* work_dev, void* stream);
 size_t spec_gemm_workspace_bytes(int M, int N, int K);
+/* How that kernel divides its work (host-only, no GPU needed): out6 = { S = K slices, most K steps of 32 a wave
+ * takes (at most 8), Gs = groups of workgroups along N, number of 16-row panels, number of K steps, 16-row tiles
+ * of x (1 or 2) }.  workgroups_per_cu is 1 or 2; S does not depend on it.  SPEC_E_INVAL for shapes spec_gemm
+ * refuses. */
+int spec_gemm_plan_query(int M, int N, int K, int workgroups_per_cu, int* out6);
 /* Only the streaming kernel of spec_gemm (no reduction pass); used to time it in isolation. */
 int spec_gemm_partials(const void* x_dev, const void* w_packed_dev, int M, int N, int K,
                        void* work_dev, void* stream);

@@ -70,6 +70,7 @@ SIGNATURES = {
     "spec_last_error": (C.c_char_p, []),
     "spec_pack_weight": (C.c_int, [_P, _P, C.c_int, C.c_int, C.c_int, C.c_int, _P]),
     "spec_packed_bytes": (C.c_size_t, [C.c_int, C.c_int]),
+    "spec_gemm_plan_query": (C.c_int, [C.c_int, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_int)]),
     "spec_gemm": (C.c_int, [_P, _P, _P, C.c_int, C.c_int, C.c_int, _P, _P]),
     "spec_gemm_workspace_bytes": (C.c_size_t, [C.c_int, C.c_int, C.c_int]),
     "spec_gemm_partials": (C.c_int, [_P, _P, C.c_int, C.c_int, C.c_int, _P, _P]),

@@ -875,6 +875,15 @@ extern "C" size_t spec_gemm_workspace_bytes(int M, int N, int K) {
   if (check_gemm_args(M, N, K)) return 0;
   return gemm_plan(M, N, K).partial_bytes();
 }
+extern "C" int spec_gemm_plan_query(int M, int N, int K, int workgroups_per_cu, int* out6) {
+  if (!out6) FAIL(SPEC_E_INVAL, "null pointer");
+  if (workgroups_per_cu != 1 && workgroups_per_cu != 2) FAIL(SPEC_E_INVAL, "workgroups_per_cu must be 1 or 2");
+  int rc = check_gemm_args(M, N, K);
+  if (rc) return rc;
+  const GemmPlan p = gemm_plan(M, N, K, workgroups_per_cu);
+  out6[0] = p.S; out6[1] = p.spw; out6[2] = p.Gs; out6[3] = p.NT; out6[4] = p.steps; out6[5] = p.MT;
+  return SPEC_OK;
+}
 extern "C" int spec_gemm_partials(const void* x, const void* w, int M, int N, int K, void* work, void* stream) {
   if (!x || !w || !work) FAIL(SPEC_E_INVAL, "null pointer");
   int rc = check_gemm_args(M, N, K);
