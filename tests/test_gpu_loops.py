@@ -85,7 +85,7 @@ def _oracle_steps(algo, tm, dm, prompt, n_generate, gamma, uni, cfg, temperature
 # (gamma 1: every post-verify row is also the last one; gamma 15: 30 pending drafts, 16-row verifies) and a sharper
 # distribution
 LOOP_CASES = [(0, 4, 1.0), (1, 4, 1.0), (2, 4, 1.0), (1, 1, 1.0), (2, 1, 1.0), (2, 2, 1.0), (1, 15, 1.0), (2, 15, 1.0),
-              (1, 6, 0.7), (2, 6, 0.7)]
+              (1, 6, 0.7), (2, 6, 0.7), (1, 16, 1.0), (2, 16, 1.0)]   # gamma 16: SD verifies 17 rows (two row tiles)
 
 
 @pytest.mark.parametrize("algo,gamma,temperature", LOOP_CASES)
