@@ -238,3 +238,33 @@ def test_gamma_calibration_leaves_the_state_as_it_found_it():
     out, _ = ctx.generate(amd.ALGO_PEARL, 4, 16, uni)
     assert out == ref
     ctx.close()
+
+
+@pytest.mark.parametrize("algo", [1, 2])
+def test_sampled_loops_at_the_benchmark_context_length(algo):
+    """SD and PEARL at gamma 7 behind a 4096-token prompt (64 pages, the largest K/V split counts, rollbacks that
+    cross page boundaries), step by step against the oracle until the first sub-margin split, if any.  Behind so
+    long a random prompt the tiny model's logits span only 2 units, and at temperature 1 a thousand tokens share
+    the mass (every step then holds a draw within 1e-4 of a CDF edge); temperature 0.15 gives distributions as
+    peaked as the short-context cases have."""
+    cfg = synth.config("tiny")
+    cfg.n_prompt, cfg.n_generate = 4096, 64
+    amd, harness, target, draft, tm, dm = _pair(cfg)
+    gamma, n_gen, temperature = 7, 48, 0.15
+    prompt = synth.prompt_tokens(cfg.n_prompt, cfg.target.vocab, 17).tolist()
+    uni = NpUniforms(synth.make_uniforms(n_gen + 1, gamma, 23))
+    ctx = harness.make_context(cfg, target, draft, gamma, temperature=temperature, extra_seq=64)
+    print(f"algo={algo}: oracle over a {len(prompt)}-token prompt", flush=True)
+    ref = _oracle_steps(algo, tm, dm, prompt, n_gen, gamma, uni, cfg, temperature)
+    ctx.prefill(prompt)
+    got = _gpu_steps(amd, ctx, algo, gamma, n_gen, uni)
+    k = 0
+    while k < min(len(ref), len(got)) and ref[k]["tokens"] == got[k]["tokens"]:
+        k += 1
+    print(f"  {k} of {len(ref)} steps agree", flush=True)
+    if k < min(len(ref), len(got)):
+        print(f"  split at step {k}: oracle margin {ref[k]['margin']:.4f}", flush=True)
+        assert ref[k]["margin"] < MARGIN_TOL, (k, ref[k], got[k])
+    assert k >= 4
+    assert ctx.kv_len(amd.SPEC_TARGET) == ctx.committed_len() - 1
+    ctx.close()
