@@ -320,3 +320,29 @@ def test_sampled_pearl_leaves_caches_as_if_never_speculated():
     clean.feed(full[:n_check])
     np.testing.assert_allclose(t.cache.k[:, :n_check], clean.cache.k[:, :n_check], rtol=0, atol=1e-10)
     np.testing.assert_allclose(t.cache.v[:, :n_check], clean.cache.v[:, :n_check], rtol=0, atol=1e-10)
+
+
+def test_draft_placement_beside_a_pipelined_target_matches_the_worked_example():
+    """The paper's multi-GPU answer to co-location (appendix on resource-constrained scenarios), as a design aid:
+    the displayed occupancy sequences for c = 5, g = 4 (fixture) and no slot with both models on one device there;
+    for every window gamma = c the placement is collision-free exactly when the first half of the drafting ends
+    before the target reaches the last device and not before it has left the first one."""
+    from oracle import placement
+    rows = {}
+    for line in open(os.path.join(GOLDEN, "rc_occupancy.txt")):
+        line = line.split("#")[0].split()
+        if line:
+            rows[line[0]] = [int(v) for v in line[1:]]
+    target, draft = placement.occupancy(5, 4, 5)
+    assert target == rows["target"] and draft == rows["draft"]
+    assert placement.collisions(5, 4, 5) == 0
+    # gamma = c (the calibrated window): collision-free when the first ceil(gamma/2) tokens (g slots each) end no
+    # later than the target reaches the last device, (g-1)*c, and the target has left device 0 (c slots) by then
+    for g in range(2, 9):
+        for c in range(1, 17):
+            first = -(-c // 2)
+            free = first * g <= (g - 1) * c and first * g >= c
+            assert (placement.collisions(c, g, c) == 0) == free, (c, g)
+    assert placement.collisions(5, 2, 5) > 0          # two devices are too few at c = 5
+    with pytest.raises(ValueError):
+        placement.occupancy(5, 1, 5)
