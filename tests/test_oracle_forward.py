@@ -178,3 +178,22 @@ def test_gqa_equals_mha_with_repeated_kv_heads():
     a = transformer.CachedModel(oracle_model(w, shape_g, np.float64), 8).feed(toks)
     b = transformer.CachedModel(oracle_model(wm, shape_m, np.float64), 8).feed(toks)
     np.testing.assert_allclose(a, b, rtol=1e-11, atol=1e-12)
+
+
+def test_byte_model_of_the_benchmark_against_the_papers_kv_cache_example():
+    """The byte counts behind every GB/s figure of the benchmark.  KV cache: the paper's appendix on
+    resource-constrained scenarios works out 2 x 2 x 32 x 1 x 8 x 1024 x 128 bytes (K and V, 2-byte elements, 32
+    layers, batch 1, 8 KV heads, 1024 tokens, head_dim 128), about 0.13 GB, for an 8B GQA model; weights: every
+    matrix of a layer once plus the LM head, 2 bytes each."""
+    import bench
+    llama8b = synth.ModelShape(32, 4096, 32, 8, 14336, 128256)
+    assert llama8b.head_dim == 128
+    kv = 1024 * llama8b.kv_bytes_per_token()
+    assert kv == 2 * 2 * 32 * 1 * 8 * 1024 * 128 and abs(kv / 1e9 - 0.13) < 0.005
+    # the 70B shape of the benchmark: 4096 B per token and layer, 80 layers
+    t70 = synth.config("70b_7b").target
+    assert t70.kv_bytes_per_token() == 80 * 4096 == 327680
+    per_layer = 8192 * (64 + 2 * 8) * 128 + 64 * 128 * 8192 + 3 * 8192 * 28672
+    assert t70.params_per_layer() == per_layer and t70.streamed_params() == 80 * per_layer + 32000 * 8192
+    n, m = 4096, 7
+    assert bench.forward_bytes(t70, n, m) == 2 * t70.streamed_params() + (n + m) * 327680 + m * 32000 * 4
