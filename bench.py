@@ -84,30 +84,37 @@ def cpu_baseline(cfg, gamma, device):
     mk = lambda w, s: transformer.Model(to_np(w), s.n_heads, s.n_kv_heads, s.head_dim, s.rope_theta, s.rms_eps)
     tm, dm = mk(tw, small.target), mk(dw, small.draft)
     del tw, dw
-    n_prompt, n_steps = 64, 3
+    n_prompt, budget_s = 64, 5.0
     prompt = synth.prompt_tokens(n_prompt, cfg.target.vocab, cfg.seed_prompt).tolist()
-    ct, cd = transformer.CachedModel(tm, 256), transformer.CachedModel(dm, 256)
-    ct.feed(prompt[:-1]); cd.feed(prompt[:-1])
-    # time the two passes of a step separately so that they can be scaled to the full depths
-    t0 = time.perf_counter()
-    for i in range(n_steps):
-        ct.feed([prompt[i]])
-    t_target = (time.perf_counter() - t0) / n_steps
-    t0 = time.perf_counter()
-    for i in range(n_steps * 2):
-        cd.feed([prompt[i]])
-    t_draft = (time.perf_counter() - t0) / (n_steps * 2)
-    # split each into per-layer and head parts with a second measurement on the LM head alone
-    x = np.ones((1, cfg.target.d_model), dtype=np.float32)
-    t0 = time.perf_counter()
-    for _ in range(3):
-        _ = x @ tm.lm_head.T
-    t_head_t = (time.perf_counter() - t0) / 3
-    x = np.ones((1, cfg.draft.d_model), dtype=np.float32)
-    t0 = time.perf_counter()
-    for _ in range(3):
-        _ = x @ dm.lm_head.T
-    t_head_d = (time.perf_counter() - t0) / 3
+    n_cache = 2048
+
+    def forwards_for(model, seconds):
+        """Single-token forwards behind the prompt for about `seconds` (at least 5, after 2 untimed ones)."""
+        cm = transformer.CachedModel(model, n_cache)
+        cm.feed(prompt[:-1])
+        for i in range(2):
+            cm.feed([prompt[i]])
+        n, t0 = 0, time.perf_counter()
+        while (n < 5 or time.perf_counter() - t0 < seconds) and cm.len < n_cache - 1:
+            cm.feed([prompt[n % n_prompt]])
+            n += 1
+        return (time.perf_counter() - t0) / n, n
+
+    def head_time(model, d_model):
+        x = np.ones((1, d_model), dtype=np.float32)
+        for _ in range(2):
+            _ = x @ model.lm_head.T
+        t0 = time.perf_counter()
+        for _ in range(10):
+            _ = x @ model.lm_head.T
+        return (time.perf_counter() - t0) / 10
+
+    # time the two passes of a step separately so that they can be scaled to the full depths, and split each
+    # into per-layer and head parts with a second measurement on the LM head alone
+    t_target, n_t = forwards_for(tm, budget_s)
+    t_draft, n_d = forwards_for(dm, budget_s)
+    t_head_t = head_time(tm, cfg.target.d_model)
+    t_head_d = head_time(dm, cfg.draft.d_model)
     per_layer_t = max(t_target - t_head_t, 0.0) / lt
     per_layer_d = max(t_draft - t_head_d, 0.0) / ld
     full_t = per_layer_t * cfg.target.n_layers + t_head_t
@@ -117,8 +124,9 @@ def cpu_baseline(cfg, gamma, device):
     step = full_t + gamma * full_d
     return {"value": 1.0 / step, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
             "sample": (f"oracle forward timed on a depth-truncated {cfg.name} pair ({lt} target + {ld} draft layers, "
-                       f"same widths, {n_prompt}-token context, {n_steps} target and {2 * n_steps} draft single-token "
-                       f"forwards); per-layer time x full depth + LM head; one PEARL step = 1 target + {gamma} draft "
+                       f"same widths, {n_prompt}-token prompt, {n_t} target and {n_d} draft single-token forwards, "
+                       f"about {budget_s:.0f} s of CPU work each after 2 untimed ones); per-layer time x full depth + LM "
+                       f"head; one PEARL step = 1 target + {gamma} draft "
                        f"forwards in series, counted at its floor of 1 committed token per step"),
             "target_forward_s": full_t, "draft_forward_s": full_d}
 
