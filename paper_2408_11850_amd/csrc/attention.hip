@@ -117,7 +117,7 @@ __global__ __launch_bounds__(256) void attn_split_kernel(const bf16* __restrict_
   l_run += __shfl_xor(l_run, 16);
   l_run += __shfl_xor(l_run, 32);
   if (valid) {
-    const size_t row = ((size_t)split * Hkv + kvh) * Rpad + Rr;
+    const size_t row = ((size_t)kvh * Rpad + Rr) * nsplit + split;   // the splits of a query row lie side by side
 #pragma unroll
     for (int dt = 0; dt < DH / 16; ++dt)
       *reinterpret_cast<f32x4*>(opart + row * DH + dt * 16 + g4 * 4) = o[dt];
@@ -147,7 +147,7 @@ __global__ __launch_bounds__(128 * MERGE_WAYS) void attn_merge_kernel(const floa
 #pragma unroll
     for (int k = 0; k < MERGE_UNROLL; ++k) {
       const int sk = s + k * MERGE_WAYS;
-      const size_t row = ((size_t)(sk < nsplit ? sk : s) * Hkv + kvh) * Rpad + Rr;
+      const size_t row = ((size_t)kvh * Rpad + Rr) * nsplit + (sk < nsplit ? sk : s);
       const bool in = sk < nsplit;
       ms[k] = in ? mlpart[row * 2] : NEG_BIG;
       ls[k] = in ? mlpart[row * 2 + 1] : 0.f;
