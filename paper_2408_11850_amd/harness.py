@@ -14,11 +14,12 @@ from .binding import PackedModel, SpecContext, pack_from_dict, pack_model
 def _generated_model(shape: synth.ModelShape, seed: int, device: str) -> PackedModel:
     """Generate each tensor on the device with the counter-based generator, pack it, drop the source."""
     mats = synth.layer_matrix_shapes(shape)
-    ones = lambda: torch.ones(shape.d_model, dtype=torch.bfloat16, device=device)
 
     def get(layer: Optional[int], name: str) -> torch.Tensor:
-        if name in ("final_norm", "attn_norm", "ffn_norm"):
-            return ones()
+        if name == "final_norm":
+            return synth.gain_tensor(shape.d_model, seed, synth._GLOBAL[name], torch.bfloat16, device)
+        if name in ("attn_norm", "ffn_norm"):
+            return synth.gain_tensor(shape.d_model, seed, 16 * layer + synth._SLOT[name], torch.bfloat16, device)
         if layer is None:
             return synth.normal_tensor((shape.vocab, shape.d_model), 0.02, seed, synth._GLOBAL[name], torch.bfloat16,
                                        device)
@@ -103,30 +104,7 @@ def make_context(cfg: synth.PairConfig, target: PackedModel, draft: PackedModel,
                        on_close=destroy if raw else None)
 
 
-def calibrate_gamma(ctx: SpecContext, n_iter: int = 8, cap: int = 16) -> Tuple[int, float, float]:
-    """Window size gamma = round(c), c = T(target forward) / T(draft forward) (paper Section 4.4.1),
-    both timed alone at the current context length.  Leaves the caches as it found them."""
-    lt, ld = ctx.kv_len(SPEC_TARGET), ctx.kv_len(SPEC_DRAFT)
-    ctx.verify([0])                      # untimed: the first forward of a shape also captures its graphs
-    ctx.rollback_kv(SPEC_TARGET, lt)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(n_iter):
-        ctx.verify([0])
-    torch.cuda.synchronize()
-    tp = (time.perf_counter() - t0) / n_iter
-    ctx.rollback_kv(SPEC_TARGET, lt)
-    ctx.draft_step(0.5)
-    ctx.drop_drafts()
-    ctx.rollback_kv(SPEC_DRAFT, ld)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    n_d = min(n_iter, 2 * ctx.gamma_max)
-    for _ in range(n_d):
-        ctx.draft_step(0.5)
-    torch.cuda.synchronize()
-    tq = (time.perf_counter() - t0) / n_d
-    ctx.drop_drafts()
-    ctx.rollback_kv(SPEC_DRAFT, ld)
-    gamma = max(1, min(cap, int(round(tp / tq))))
-    return gamma, tp, tq
+def calibrate_gamma(ctx: SpecContext, n_iter: int = 8, cap: int = 16, concurrent: bool = False) -> Tuple[int, float, float]:
+    """Window size gamma = round(c), c = T(target forward) / T(draft forward) (paper Section 4.4.1): computed by the
+    library (spec_calibrate_gamma); leaves the caches as it found them."""
+    return ctx.calibrate_gamma(n_iter, cap, concurrent)

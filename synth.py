@@ -182,8 +182,17 @@ def config(name: str, depth: Optional[int] = None, draft_depth: Optional[int] = 
 
 
 # tensor ids: per-layer matrices get id = 16*layer + slot; globals sit above 1<<20
-_SLOT = {"wq": 0, "wk": 1, "wv": 2, "wo": 3, "w_gate": 4, "w_up": 5, "w_down": 6}
-_GLOBAL = {"tok_embed": (1 << 20) + 0, "lm_head": (1 << 20) + 1}
+_SLOT = {"wq": 0, "wk": 1, "wv": 2, "wo": 3, "w_gate": 4, "w_up": 5, "w_down": 6, "attn_norm": 7, "ffn_norm": 8}
+_GLOBAL = {"tok_embed": (1 << 20) + 0, "lm_head": (1 << 20) + 1, "final_norm": (1 << 20) + 2}
+GAIN_STD = 0.3      # RMSNorm gains are 1 + GAIN_STD * N(0,1), a different vector per norm
+
+
+def gain_tensor(d_model: int, seed: int, tensor_id: int, dtype: torch.dtype, device="cpu") -> torch.Tensor:
+    """RMSNorm gain vector 1 + GAIN_STD * N(0,1) (distinct per tensor id), rounded to `dtype`.  Trained models have
+    non-trivial gains; with all-ones gains a kernel that dropped the multiply or took the wrong vector would go
+    unnoticed."""
+    z = normal_tensor((d_model,), GAIN_STD, seed, tensor_id, torch.float64, device)
+    return (1.0 + z).to(dtype)
 
 
 def layer_matrix_shapes(s: ModelShape) -> Dict[str, tuple]:
@@ -194,15 +203,15 @@ def layer_matrix_shapes(s: ModelShape) -> Dict[str, tuple]:
 
 
 def make_weights(shape: ModelShape, seed: int, dtype: torch.dtype, device="cpu", std: float = 0.02) -> dict:
-    """Random-init decoder weights: matrices N(0, std^2) rounded to `dtype`, all norm gains 1."""
+    """Random-init decoder weights: matrices N(0, std^2) and norm gains 1 + GAIN_STD * N(0,1), rounded to `dtype`."""
     w = {"tok_embed": normal_tensor((shape.vocab, shape.d_model), std, seed, _GLOBAL["tok_embed"], dtype, device),
          "lm_head": normal_tensor((shape.vocab, shape.d_model), std, seed, _GLOBAL["lm_head"], dtype, device),
-         "final_norm": torch.ones(shape.d_model, dtype=dtype, device=device),
+         "final_norm": gain_tensor(shape.d_model, seed, _GLOBAL["final_norm"], dtype, device),
          "layers": []}
     mats = layer_matrix_shapes(shape)
     for l in range(shape.n_layers):
-        lay = {"attn_norm": torch.ones(shape.d_model, dtype=dtype, device=device),
-               "ffn_norm": torch.ones(shape.d_model, dtype=dtype, device=device)}
+        lay = {"attn_norm": gain_tensor(shape.d_model, seed, 16 * l + _SLOT["attn_norm"], dtype, device),
+               "ffn_norm": gain_tensor(shape.d_model, seed, 16 * l + _SLOT["ffn_norm"], dtype, device)}
         for name, shp in mats.items():
             lay[name] = normal_tensor(shp, std, seed, 16 * l + _SLOT[name], dtype, device)
         w["layers"].append(lay)
