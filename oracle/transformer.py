@@ -8,6 +8,19 @@ projection + residual -> RMSNorm -> SwiGLU FFN + residual; final RMSNorm -> LM h
 
 All matrices are [out_features, in_features] (y = x @ W.T).  Arithmetic runs in the
 dtype of `Model.dtype` (float32 by default, float64 for pins).
+
+Precision.  The paper runs its models in bfloat16 (App. C: weights loaded in bf16).  The plain
+forward above keeps every activation in `dtype`; with `act_bf16=True` the same forward rounds
+the activations that a bf16 deployment hands from one operator to the next to bfloat16
+(round-to-nearest-even) - the input of each projection, q / k / v after RoPE (k, v are what
+the cache holds), the soft-max weights that multiply v, the attention output and the SwiGLU
+product - while sums, the residual stream, norms' statistics, soft-max and logits stay in
+`dtype`.  The input of a projection is rounded as h * gain and the factor 1/rms is applied to
+the projection's output (the projection is linear, so this is the same operator; bf16 has the
+same relative step at any scale, so it is also the same amount of rounding).  The variant
+exists to tell rounding noise from mistakes: the distance between the two variants is what
+bf16 activations cost at a given depth, and an implementation with these rounding points
+should sit much closer to the rounded variant than to the plain one.
 """
 from __future__ import annotations
 
@@ -18,8 +31,9 @@ class Model:
     """Weights of one decoder.  `w` mirrors the generator's dict layout, as NumPy arrays."""
 
     def __init__(self, w: dict, n_heads: int, n_kv_heads: int, head_dim: int,
-                 rope_theta: float = 10000.0, rms_eps: float = 1e-5, dtype=np.float32):
+                 rope_theta: float = 10000.0, rms_eps: float = 1e-5, dtype=np.float32, act_bf16: bool = False):
         self.dtype = dtype
+        self.act_bf16 = act_bf16
         cv = lambda a: np.ascontiguousarray(np.asarray(a, dtype=dtype))
         self.tok_embed = cv(w["tok_embed"])
         self.lm_head = cv(w["lm_head"])
@@ -45,10 +59,28 @@ class KVCache:
         self.len = new_len
 
 
+def bf16_round(x):
+    """Round to the nearest bfloat16 (ties to even), returned in x's dtype.  bfloat16 = the upper 16 bits of an
+    IEEE float32; finite inputs only."""
+    x = np.asarray(x)
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    r = (u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))) & np.uint32(0xFFFF0000)
+    return r.view(np.float32).astype(x.dtype)
+
+
 def rmsnorm(x, gain, eps):
     """x / sqrt(mean(x^2) + eps) * gain, per row."""
     ms = np.mean(x * x, axis=-1, keepdims=True)
     return x / np.sqrt(ms + x.dtype.type(eps)) * gain
+
+
+def norm_input(model, h, gain):
+    """(a, scale) with norm(h) @ W.T == (a @ W.T) * scale: plainly a = rmsnorm(h) and scale = 1; with bf16
+    activations a = bf16(h * gain) and scale = 1/rms(h), per row."""
+    if not model.act_bf16:
+        return rmsnorm(h, gain, model.rms_eps), h.dtype.type(1.0)
+    ms = np.mean(h * h, axis=-1, keepdims=True)
+    return bf16_round(h * gain), 1.0 / np.sqrt(ms + h.dtype.type(model.rms_eps))
 
 
 def rope(x, positions, theta):
@@ -83,14 +115,15 @@ def forward(model: Model, cache: KVCache, tokens) -> np.ndarray:
     group = H // Hkv
     pos = np.arange(n, n + M)
     scale = model.dtype(1.0 / np.sqrt(D))
+    rb = bf16_round if model.act_bf16 else (lambda x: x)
     h = model.tok_embed[tokens]                                   # [M, d]
     for l, w in enumerate(model.layers):
-        a = rmsnorm(h, w["attn_norm"], model.rms_eps)
-        q = (a @ w["wq"].T).reshape(M, H, D)
-        k = (a @ w["wk"].T).reshape(M, Hkv, D)
-        v = (a @ w["wv"].T).reshape(M, Hkv, D)
-        q = rope(q, pos, model.rope_theta)
-        k = rope(k, pos, model.rope_theta)
+        a, sc = norm_input(model, h, w["attn_norm"])
+        q = ((a @ w["wq"].T) * sc).reshape(M, H, D)
+        k = ((a @ w["wk"].T) * sc).reshape(M, Hkv, D)
+        v = rb(((a @ w["wv"].T) * sc).reshape(M, Hkv, D))
+        q = rb(rope(q, pos, model.rope_theta))
+        k = rb(rope(k, pos, model.rope_theta))
         cache.k[l, n:n + M] = k
         cache.v[l, n:n + M] = v
         o = np.zeros((M, H, D), dtype=model.dtype)
@@ -101,14 +134,14 @@ def forward(model: Model, cache: KVCache, tokens) -> np.ndarray:
                 s = (cache.k[l, :T, kv] @ q[i, j]) * scale        # [T]
                 s = s - s.max()
                 p = np.exp(s)
-                p = p / p.sum()
-                o[i, j] = p @ cache.v[l, :T, kv]
-        h = h + o.reshape(M, H * D) @ w["wo"].T
-        b = rmsnorm(h, w["ffn_norm"], model.rms_eps)
-        z = silu(b @ w["w_gate"].T) * (b @ w["w_up"].T)
+                o[i, j] = (rb(p) @ cache.v[l, :T, kv]) / p.sum()   # = softmax(s) @ V; the weights on V rounded if asked
+        h = h + rb(o.reshape(M, H * D)) @ w["wo"].T
+        b, sc = norm_input(model, h, w["ffn_norm"])
+        z = rb(silu((b @ w["w_gate"].T) * sc) * ((b @ w["w_up"].T) * sc))
         h = h + z @ w["w_down"].T
     cache.len = n + M
-    return rmsnorm(h, model.final_norm, model.rms_eps) @ model.lm_head.T
+    a, sc = norm_input(model, h, model.final_norm)
+    return (a @ model.lm_head.T) * sc
 
 
 class CachedModel:

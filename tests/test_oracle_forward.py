@@ -197,3 +197,71 @@ def test_byte_model_of_the_benchmark_against_the_papers_kv_cache_example():
     assert t70.params_per_layer() == per_layer and t70.streamed_params() == 80 * per_layer + 32000 * 8192
     n, m = 4096, 7
     assert bench.forward_bytes(t70, n, m) == 2 * t70.streamed_params() + (n + m) * 327680 + m * 32000 * 4
+
+
+def test_bf16_round_is_round_to_nearest_even_on_the_upper_16_bits():
+    f = lambda v: float(transformer.bf16_round(np.array([v], dtype=np.float32))[0])
+    assert f(1.0) == 1.0 and f(-2.5) == -2.5 and f(0.0) == 0.0
+    ulp = 2.0 ** -7                                    # spacing of bfloat16 in [1, 2): 8 significant bits
+    assert f(1.0 + 0.49 * ulp) == 1.0 and f(1.0 + 0.51 * ulp) == 1.0 + ulp
+    assert f(1.0 + 0.5 * ulp) == 1.0                   # tie -> even mantissa
+    assert f(1.0 + 1.5 * ulp) == 1.0 + 2 * ulp         # tie -> even mantissa (upwards)
+    assert f(-(1.0 + 1.5 * ulp)) == -(1.0 + 2 * ulp)
+    x = np.random.default_rng(0).standard_normal(10000).astype(np.float32) * 37.0
+    r = transformer.bf16_round(x)
+    assert np.array_equal(transformer.bf16_round(r), r)                      # idempotent
+    assert np.all(np.abs(r - x) <= np.abs(x) * 2.0 ** -8)                    # half an ulp, relative
+    assert np.array_equal(r, torch.from_numpy(x).to(torch.bfloat16).float().numpy())   # the library conversion
+    assert transformer.bf16_round(x.astype(np.float64)).dtype == np.float64
+
+
+def test_bf16_activation_variant_is_the_same_forward_up_to_rounding_noise():
+    """act_bf16 only rounds activations: with it off nothing changes; with it on the logits move by an amount of
+    the order of bf16's 2^-9 relative step (not zero, not large), and a multi-token feed still equals token-by-token
+    feeds up to that noise."""
+    cfg = synth.config("tiny")
+    tw, _ = synth.make_pair(cfg)
+    w = {"tok_embed": tw["tok_embed"].numpy(), "lm_head": tw["lm_head"].numpy(), "final_norm": tw["final_norm"].numpy(),
+         "layers": [{k: v.numpy() for k, v in lay.items()} for lay in tw["layers"]]}
+    s = cfg.target
+    plain = transformer.Model(w, s.n_heads, s.n_kv_heads, s.head_dim, dtype=np.float64)
+    rounded = transformer.Model(w, s.n_heads, s.n_kv_heads, s.head_dim, dtype=np.float64, act_bf16=True)
+    toks = synth.prompt_tokens(24, s.vocab, 3).tolist()
+    a = transformer.CachedModel(plain, 32).feed(toks)
+    b = transformer.CachedModel(rounded, 32).feed(toks)
+    rng = a.max(axis=-1) - a.min(axis=-1)
+    err = (np.abs(a - b).max(axis=-1) / rng).max()
+    assert 2e-4 < err < 8e-3, err
+    c = transformer.CachedModel(rounded, 32)
+    seq = np.concatenate([c.feed([t]) for t in toks])
+    assert (np.abs(seq - b).max(axis=-1) / rng).max() < 8e-3
+
+
+def test_bf16_activation_noise_grows_with_depth_only_where_the_weights_amplify():
+    """What bf16 activations cost against exact arithmetic in a random-init decoder, by depth (no GPU involved).
+    With N(0, std^2) matrices a projection multiplies the scale of its (normalised) input by about std * sqrt(d).
+    Below 1 (std 0.02 at d = 512) every layer's rounding noise stays what it was: the logit error is flat in depth.
+    At 1.81 (std 0.08 at d = 512; the value the benchmark's 70B shape has with std 0.02 at d = 8192) a perturbation
+    grows from layer to layer: 1e-2 of the logits' range at 2 layers, past 2e-2 by 8, past 5e-2 by 32.  So a bound
+    of 2e-2 against fp32 cannot hold at depth for any bf16-activation implementation of that shape; the GPU tests
+    assert it where it can hold and compare deeper stacks with the bf16-activation variant as well."""
+    shape = synth.ModelShape(32, 512, 8, 2, 1376, 2048)
+    prompt = synth.prompt_tokens(64, shape.vocab, 7).tolist()
+    curves = {}
+    for std in (0.02, 0.08):
+        w = synth.make_weights(shape, 1234, torch.bfloat16, std=std)
+        wn = {"tok_embed": w["tok_embed"].float().numpy(), "lm_head": w["lm_head"].float().numpy(),
+              "final_norm": w["final_norm"].float().numpy(),
+              "layers": [{k: v.float().numpy() for k, v in lay.items()} for lay in w["layers"]]}
+        for depth in (2, 8, 32):
+            wk = dict(wn, layers=wn["layers"][:depth])
+            mk = lambda r, dt: transformer.CachedModel(transformer.Model(wk, 8, 2, 64, dtype=dt, act_bf16=r), 80)
+            exact = mk(False, np.float64).feed(prompt)[-8:]
+            noisy = mk(True, np.float32).feed(prompt)[-8:]
+            rng = exact.max(-1) - exact.min(-1)
+            curves[(std, depth)] = float((np.abs(exact - noisy).max(-1) / rng).mean())
+    print(curves)
+    flat = [curves[(0.02, d)] for d in (2, 8, 32)]
+    steep = [curves[(0.08, d)] for d in (2, 8, 32)]
+    assert max(flat) < 5e-3 and max(flat) < 1.6 * min(flat)
+    assert steep[0] < 1.5e-2 and steep[1] > 1.5 * steep[0] and steep[2] > 1.5 * steep[1] and steep[2] > 3e-2
