@@ -1,10 +1,10 @@
 /*
  * spec.h - C ABI of the MI355X (gfx950) library for parallel speculative decoding (PEARL).
  *
- * One context holds a target model M_p and a draft model M_q (paper, Section 2 "Notations"),
- * a paged KV cache per model, a cache of draft distributions q_i (Algorithm 2, "retrieval of
- * q_1..q_gamma from the cache") and two HIP streams so that drafting and verification overlap
- * (Section 3.4 "Parallelism").  All arithmetic of the decoding path runs in this library's
+ * One context holds a target model M_p and a draft model M_q (paper, Section 2, notations),
+ * a paged KV cache per model, a cache of the draft distributions q_i that a later verification
+ * reads back (Algorithm 2) and two HIP streams so that drafting and verification overlap
+ * (Section 3.4).  All arithmetic of the decoding path runs in this library's
  * kernels; callers only provide device memory for the weights and the two streams.
  *
  * Conventions
@@ -13,7 +13,7 @@
  *   - "device" pointers are HIP device memory on the current device, "host" pointers are
  *     ordinary host memory.  Weights and streams are BORROWED: they must outlive the context.
  *   - a context is not thread-safe; calls on one context must come from one thread at a time.
- *   - uniform random numbers are inputs (host floats in (0,1)), never drawn inside the library.
+ *   - uniform random numbers are inputs (host floats in [0,1)), never drawn inside the library.
  *
  * Weight layouts (all bf16)
  *   - tok_embed      : row-major [vocab][d_model]
@@ -102,7 +102,10 @@ void spec_free(spec_ctx* ctx);
 
 /* Reset both caches and feed prompt[0..n-2] to both models; prompt[n-1] becomes the frontier
  * (the last committed token, the one token neither cache holds yet); mode := pre-verify.
- * This realises "M_p(x), M_q(x) on the prefix" of Algorithm 2 with a KV cache.  Synchronous.
+ * This is the evaluation of both models on the prefix in Algorithm 2, done with a KV cache.  Synchronous.
+ * Errors found before anything is touched (bad arguments, a prompt that cannot fit) leave the context as it
+ * was; a failure after the caches have been reset leaves it un-prefilled: every decoding call then returns
+ * SPEC_E_STATE until a spec_prefill succeeds.
  * `which_mask`: bit SPEC_TARGET / bit SPEC_DRAFT select the models to prefill (3 = both). */
 int spec_prefill(spec_ctx* ctx, const int32_t* prompt_host, int n_prompt, int which_mask);
 
@@ -140,8 +143,9 @@ int spec_accept(spec_ctx* ctx, int kind, const float* r_host, int n_r, float u_r
                 int* n_accepted, int32_t* tokens_out_host, int* n_out, int* next_mode, int* keep_len);
 
 /* Drop everything after the first new_len tokens of one model's cache: O(1) - sets the length
- * and returns whole pages to the pool (Figure 3: "drops x10, x11, x12").  Unverified drafts that
- * lie beyond the new length are forgotten.  SPEC_E_INVAL if new_len > current length. */
+ * and returns whole pages to the pool (the discarding of the newer drafts after a rejection in
+ * Figure 3).  Unverified drafts that lie beyond the new length are forgotten.  SPEC_E_INVAL if
+ * new_len > current length. */
 int spec_rollback_kv(spec_ctx* ctx, int which, int new_len);
 
 /* Forget every unverified draft token and its q row (the caller rolls the draft cache back itself). */
@@ -165,13 +169,24 @@ long long spec_forward_count(const spec_ctx* ctx, int which); /* forwards run so
  * by step: u_draft[t*gamma + i], r_accept[t*(gamma+1) + i], u_resample[t]; each must hold
  * n_generate steps (2 n_generate for algo 3, whose draft-only steps commit nothing).  The loop ends after n_generate tokens, or after max_steps steps if
  * max_steps > 0.  force_bits == NULL uses real decisions; otherwise decision (t, i) is taken
- * from force_bits[t*(gamma+1)+i] (measurement only).  out_tokens_host receives the committed
+ * from force_bits[t*(gamma+1)+i] (measurement only).  SPEC_E_STATE if drafts of an earlier call are still
+ * pending that this loop cannot take over (any for algo 0 / 1; a number other than gamma for the PEARL variants).
+ * out_tokens_host receives the committed
  * tokens (at most n_generate; stats[1] tells how many were committed).
  * stats_host (nullable, 8 doubles): steps, committed, draft forwards, target forwards,
  * accepted, tested, post-verify steps, seconds. */
 int spec_generate(spec_ctx* ctx, int algo, int gamma, int n_generate, int max_steps, const float* u_draft,
                   const float* r_accept, const float* u_resample, const uint8_t* force_bits,
                   int32_t* out_tokens_host, double* stats_host);
+
+/* Window size of Section 4.4.1: gamma = round(c), c = T(one target forward) / T(one draft forward incl. its draw),
+ * both over one token at the current context length, clamped to [1, min(cap, gamma_max)].
+ * concurrent == 0: each model timed with the GPU to itself, n_iter forwards each (the paper's setting: one device
+ * per model).  concurrent != 0: both streams busy at once, as inside a PEARL step on one GPU (needs two streams).
+ * Needs a prefilled context between steps (no drafts pending, else SPEC_E_STATE); leaves caches, committed tokens
+ * and mode as it found them.  Outputs: *gamma_out and the two times in seconds per forward.  Synchronous. */
+int spec_calibrate_gamma(spec_ctx* ctx, int n_iter, int cap, int concurrent, int* gamma_out, double* t_target_s,
+                         double* t_draft_s);
 
 const char* spec_last_error(void);
 
@@ -239,9 +254,14 @@ int spec_accept_rows(const float* p_logits_dev, int n_rows, const float* q_rows_
  * matrix-core GEMMs and a causal flash-attention kernel (needs d_model, n_heads*head_dim and d_ffn to be
  * multiples of 32, else SPEC_E_INVAL at spec_prefill); 0 = as a sequence of 32-token verify forwards (the
  * decode kernels); -1 (default) = dense when the shapes allow it and the prompt has more than 64 tokens.
- * Both fill the caches with the same K / V up to bf16 rounding of differently ordered sums. */
-enum { SPEC_OPT_GEMM_WGS_PER_CU = 1, SPEC_OPT_GRAPHS = 2, SPEC_OPT_PREFILL = 3 };
+ * Both fill the caches with the same K / V up to bf16 rounding of differently ordered sums.
+ * SPEC_OPT_TEST_FAIL_PREFILL (tests of the error path only): n > 0 makes the next spec_prefill give up with
+ * SPEC_E_NOMEM after its n-th forward, as if the KV pages had run out half way; one-shot.
+ * spec_get_option reads a value back; for SPEC_OPT_GEMM_WGS_PER_CU it is the mode the next forward launches with
+ * (1 or 2). */
+enum { SPEC_OPT_GEMM_WGS_PER_CU = 1, SPEC_OPT_GRAPHS = 2, SPEC_OPT_PREFILL = 3, SPEC_OPT_TEST_FAIL_PREFILL = 4 };
 int spec_set_option(spec_ctx* ctx, int option, int value);
+int spec_get_option(const spec_ctx* ctx, int option, int* value);
 
 /* Run-time switches: bit 0 = record HIP events around every projection launch of the
  * target forward (read with spec_profile_read). */

@@ -23,6 +23,7 @@ ALGO_PEARL_NO_PRE, ALGO_PEARL_NO_POST = 3, 4      # the two ablations
 SPEC_OPT_GEMM_WGS_PER_CU = 1
 SPEC_OPT_GRAPHS = 2
 SPEC_OPT_PREFILL = 3
+SPEC_OPT_TEST_FAIL_PREFILL = 4
 EPI_STORE, EPI_RESID, EPI_SWIGLU = 0, 1, 2
 
 
@@ -67,6 +68,8 @@ SIGNATURES = {
     "spec_forward_count": (C.c_longlong, [_P, C.c_int]),
     "spec_generate": (C.c_int, [_P, C.c_int, C.c_int, C.c_int, C.c_int, _PF, _PF, _PF, C.POINTER(C.c_uint8), _PI32,
                                 C.POINTER(C.c_double)]),
+    "spec_calibrate_gamma": (C.c_int, [_P, C.c_int, C.c_int, C.c_int, _PI, C.POINTER(C.c_double),
+                                       C.POINTER(C.c_double)]),
     "spec_last_error": (C.c_char_p, []),
     "spec_pack_weight": (C.c_int, [_P, _P, C.c_int, C.c_int, C.c_int, C.c_int, _P]),
     "spec_packed_bytes": (C.c_size_t, [C.c_int, C.c_int]),
@@ -80,6 +83,7 @@ SIGNATURES = {
     "spec_accept_rows": (C.c_int, [_P, C.c_int, _P, _P, C.c_int, C.c_int, C.c_float, C.c_float, _PF, C.c_float,
                                    _PI32, _P]),
     "spec_set_option": (C.c_int, [_P, C.c_int, C.c_int]),
+    "spec_get_option": (C.c_int, [_P, C.c_int, _PI]),
     "spec_set_profile": (C.c_int, [_P, C.c_int]),
     "spec_profile_read": (C.c_int, [_P, C.POINTER(C.c_double), C.POINTER(C.c_longlong), C.POINTER(C.c_double)]),
 }

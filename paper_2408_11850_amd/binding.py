@@ -1,7 +1,9 @@
 """Python-side marshalling for libspec.so: packed weights, contexts, and the single-kernel calls."""
 from __future__ import annotations
 
+import atexit
 import ctypes as C
+import weakref
 from typing import Callable, List, Optional
 
 import numpy as np
@@ -114,6 +116,26 @@ def pack_from_dict(shape, w: dict, device="cuda") -> PackedModel:
     return pack_model(shape, get, device)
 
 
+_live_contexts = weakref.WeakSet()
+
+
+@atexit.register
+def _close_live_contexts():
+    """No program leaves with live HIP objects of this library: contexts still open at interpreter exit are freed
+    (graphs, events, device memory, then the streams made for them), and the device is drained before the runtime's
+    own teardown starts."""
+    for ctx in list(_live_contexts):
+        try:
+            ctx.close()
+        except Exception:
+            pass
+    try:
+        if torch.cuda.is_initialized():
+            torch.cuda.synchronize()
+    except Exception:
+        pass
+
+
 class SpecContext:
     """One target/draft pair with its caches: the calls of include/spec.h as methods."""
 
@@ -136,6 +158,7 @@ class SpecContext:
         check(self.lib.spec_init(C.byref(cfg), C.byref(td), C.byref(tw), C.byref(dd), C.byref(dw),
                                  C.byref(self._ctx)))
         self.gamma_max = gamma_max
+        _live_contexts.add(self)
 
     def close(self):
         if getattr(self, "_ctx", None):
@@ -232,8 +255,20 @@ class SpecContext:
         st = dict(zip(keys, stats.tolist()))
         return out[:min(n_out, int(st["committed"]))].tolist(), st
 
+    def calibrate_gamma(self, n_iter: int = 8, cap: int = 16, concurrent: bool = False):
+        """(gamma, seconds per target forward, seconds per draft forward): gamma = round(c) of Section 4.4.1."""
+        g, tp, tq = C.c_int(), C.c_double(), C.c_double()
+        check(self.lib.spec_calibrate_gamma(self._ctx, int(n_iter), int(cap), 1 if concurrent else 0, C.byref(g),
+                                            C.byref(tp), C.byref(tq)))
+        return g.value, tp.value, tq.value
+
     def set_option(self, option: int, value: int):
         check(self.lib.spec_set_option(self._ctx, option, value))
+
+    def get_option(self, option: int) -> int:
+        v = C.c_int()
+        check(self.lib.spec_get_option(self._ctx, option, C.byref(v)))
+        return v.value
 
     # ---- profiling -----------------------------------------------------------------------
     def set_profile(self, flags: int):

@@ -182,7 +182,7 @@ __global__ __launch_bounds__(128 * MERGE_WAYS) void attn_merge_kernel(const floa
 
 static int attn_nsplit(int Hkv, int nrt, int T) {
   const int nchunks = (T + 31) / 32;
-  int ns = (3 * SPEC_NUM_CU + Hkv * nrt - 1) / (Hkv * nrt);   // about three waves per compute unit ...
+  int ns = (3 * spec_num_cu() + Hkv * nrt - 1) / (Hkv * nrt);   // about three waves per compute unit ...
   if (ns > (nchunks + 1) / 2) ns = (nchunks + 1) / 2;           // ... but at least two chunks per split
   if (ns < 1) ns = 1;
   return ns;

@@ -24,7 +24,14 @@
 #define GEMM_LOAD(p) __builtin_nontemporal_load(p)
 #endif
 
+static int g_num_cu = 256;
+int spec_num_cu() { return g_num_cu; }
+void spec_set_num_cu(int n) {
+  if (n >= 1) g_num_cu = n;
+}
+
 GemmPlan gemm_plan(int M, int N, int K, int wgs_per_cu) {
+  const int ncu = spec_num_cu();
   GemmPlan p;
   p.M = M; p.N = N; p.K = K;
   p.steps = (K + 31) / 32;
@@ -32,7 +39,7 @@ GemmPlan gemm_plan(int M, int N, int K, int wgs_per_cu) {
   p.MT = M > 16 ? 2 : 1;
   if (p.MT == 2 || wgs_per_cu < 1) wgs_per_cu = 1;     // the 32-row variant needs a whole CU
   if (wgs_per_cu > 2) wgs_per_cu = 2;
-  const int slots = SPEC_NUM_CU * wgs_per_cu;
+  const int slots = ncu * wgs_per_cu;
   const int spwmax = 8;
   // The K split depends on the shape only, never on wgs_per_cu (always planned for two workgroups per CU), so both
   // launch modes add the same numbers in the same order.  The fewest slices a wave's 8 steps allow are not always
@@ -45,14 +52,14 @@ GemmPlan gemm_plan(int M, int N, int K, int wgs_per_cu) {
   for (int S = smin; S <= 2 * smin; ++S) {
     const int spw = (p.steps + GEMM_WAVES * S - 1) / (GEMM_WAVES * S);
     if (S > smin && spw < 4) break;
-    int Gs = 2 * SPEC_NUM_CU / S;
+    int Gs = 2 * ncu / S;
     if (Gs < 1) Gs = 1;
     if (Gs > p.NT) Gs = p.NT;
     const long long cost = (long long)((p.NT + Gs - 1) / Gs) * spw;
     if (best < 0 || cost < best) best = cost, p.S = S;
   }
   // small matrices: cut K finer until every workgroup slot (at two per CU) has work
-  while (p.S * p.NT < 2 * SPEC_NUM_CU && (p.steps + GEMM_WAVES * p.S * 2 - 1) / (GEMM_WAVES * p.S * 2) >= 2) p.S *= 2;
+  while (p.S * p.NT < 2 * ncu && (p.steps + GEMM_WAVES * p.S * 2 - 1) / (GEMM_WAVES * p.S * 2) >= 2) p.S *= 2;
   p.spw = (p.steps + GEMM_WAVES * p.S - 1) / (GEMM_WAVES * p.S);   // most steps a wave takes
   p.Gs = slots / p.S;
   if (p.Gs < 1) p.Gs = 1;
@@ -269,6 +276,6 @@ __global__ __launch_bounds__(512) void read_probe_kernel(const u32x4* __restrict
 }
 
 hipError_t launch_read_probe(const void* src, size_t bytes, void* out, hipStream_t st) {
-  read_probe_kernel<<<dim3(SPEC_NUM_CU * 4), dim3(512), 0, st>>>((const u32x4*)src, bytes / 16, (unsigned*)out);
+  read_probe_kernel<<<dim3(spec_num_cu() * 4), dim3(512), 0, st>>>((const u32x4*)src, bytes / 16, (unsigned*)out);
   return hipGetLastError();
 }

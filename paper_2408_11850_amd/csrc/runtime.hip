@@ -96,6 +96,7 @@ struct spec_ctx {
   int wgs_opt = -1;               // projection workgroups per CU: -1 = automatic, 1, 2
   int wgs = 2;                    // what the next forward uses
   int prefill_opt = -1;           // -1 automatic, 0 = 32-token verify forwards, 1 = dense path
+  int fail_prefill_after = 0;     // test hook: > 0 = the next spec_prefill gives up after that many forwards
   ProfEvents prof;
 };
 
@@ -433,6 +434,14 @@ extern "C" int spec_init(const spec_config* cfg, const spec_model_desc* target, 
   if (cfg->page_tokens != SPEC_PAGE_TOKENS) FAIL(SPEC_E_INVAL, "page_tokens must be %d", SPEC_PAGE_TOKENS);
   if (cfg->max_seq < 1) FAIL(SPEC_E_INVAL, "max_seq must be positive");
   if (!(cfg->temperature >= 0.0f) || !(cfg->logit_scale > 0.0f)) FAIL(SPEC_E_INVAL, "bad temperature / logit_scale");
+  {
+    // the work splits (K slices of the projections, attention splits) are sized for the device's compute units
+    int dev = 0, ncu = 0;
+    HIPCHK(hipGetDevice(&dev));
+    HIPCHK(hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev));
+    if (ncu < 1) FAIL(SPEC_E_HIP, "device reports %d compute units", ncu);
+    spec_set_num_cu(ncu);
+  }
   spec_ctx* c = new (std::nothrow) spec_ctx();
   if (!c) FAIL(SPEC_E_NOMEM, "out of host memory");
   c->cfg = *cfg;
@@ -493,6 +502,9 @@ extern "C" int spec_prefill(spec_ctx* c, const int32_t* prompt, int n_prompt, in
     if (((which_mask >> w) & 1) && c->prefill_opt == 1 && !dense_shapes_ok(c->m[w].d))
       FAIL(SPEC_E_INVAL, "dense prefill needs d_model, n_heads*head_dim and d_ffn to be multiples of 32");
   int rc;
+  // from here on the caches are being rebuilt: until the call has succeeded the context takes no decoding call
+  // (a prompt pass that fails half way, e.g. for lack of KV pages, must not leave a usable-looking context)
+  c->prefilled = false;
   HIPCHK(hipStreamSynchronize(c->m[0].stream));
   HIPCHK(hipStreamSynchronize(c->m[1].stream));
   for (int w = 0; w < 2; ++w)
@@ -502,6 +514,15 @@ extern "C" int spec_prefill(spec_ctx* c, const int32_t* prompt, int n_prompt, in
   c->n_prompt = n_prompt;
   c->last_verify_rows = 0;
   c->mode = SPEC_MODE_PRE;
+  int fail_after = c->fail_prefill_after;   // one-shot test hook (SPEC_OPT_TEST_FAIL_PREFILL)
+  c->fail_prefill_after = 0;
+  auto injected_failure = [&]() {
+    if (fail_after > 0 && --fail_after == 0) {
+      spec_set_error("prompt pass abandoned half way (SPEC_OPT_TEST_FAIL_PREFILL)");
+      return true;
+    }
+    return false;
+  };
   for (int w = 0; w < 2; ++w) {
     if (!((which_mask >> w) & 1)) continue;
     if (c->prefill_opt == 1 || (c->prefill_opt < 0 && dense_shapes_ok(c->m[w].d) && n_prompt - 1 > 64)) {
@@ -510,6 +531,7 @@ extern "C" int spec_prefill(spec_ctx* c, const int32_t* prompt, int n_prompt, in
       for (int s = 0; s < n_prompt - 1; s += c->m[w].pf_cap) {
         const int n = (n_prompt - 1 - s) < c->m[w].pf_cap ? (n_prompt - 1 - s) : c->m[w].pf_cap;
         if ((rc = prefill_dense_block(c, w, c->committed.data() + s, n))) return rc;
+        if (injected_failure()) return SPEC_E_NOMEM;
       }
       continue;
     }
@@ -518,6 +540,7 @@ extern "C" int spec_prefill(spec_ctx* c, const int32_t* prompt, int n_prompt, in
       src.n = (n_prompt - 1 - s) < SPEC_MAX_TOKENS ? (n_prompt - 1 - s) : SPEC_MAX_TOKENS;
       for (int i = 0; i < src.n; ++i) src.imm[i] = prompt[s + i], src.slot[i] = 0;
       if ((rc = forward(c, w, src, 0))) return rc;
+      if (injected_failure()) return SPEC_E_NOMEM;
     }
   }
   HIPCHK(hipStreamSynchronize(c->m[0].stream));
@@ -754,8 +777,20 @@ extern "C" int spec_generate(spec_ctx* c, int algo, int gamma, int n_generate, i
   if (algo > 0 && (gamma < 1 || gamma > c->cfg.gamma_max || !u_draft || !r_accept)) FAIL(SPEC_E_INVAL, "bad gamma / uniforms");
   if (n_generate < 1) FAIL(SPEC_E_INVAL, "n_generate must be positive");
   if (!c->prefilled) FAIL(SPEC_E_STATE, "spec_prefill has not run");
+  // Drafts left pending by an earlier call belong to that call's loop and window: autoregressive and vanilla
+  // speculative decoding start from none, the PEARL variants may go on where a PEARL call with the same window stopped.
+  if (algo <= 1 && c->n_drafted > 0)
+    FAIL(SPEC_E_STATE, "%d unverified drafts pending: drop them (spec_drop_drafts + spec_rollback_kv, or spec_rewind) first",
+         c->n_drafted);
+  if (algo >= 2 && c->n_drafted != 0 && c->n_drafted != gamma)
+    FAIL(SPEC_E_STATE, "%d unverified drafts pending do not fit a window of %d", c->n_drafted, gamma);
   const int g1 = gamma + 1;
-  const int wgs_before = c->wgs;
+  // the launch mode is put back on every way out of the loop, errors included
+  struct WgsGuard {
+    spec_ctx* c;
+    int saved;
+    ~WgsGuard() { c->wgs = saved; }
+  } wgs_guard{c, c->wgs};
   // while the two streams overlap, one projection workgroup per CU and stream is better from gamma 6 on (long draft chains),
   // two per CU below that (measured on the 70B/7B-shape pair)
   if (c->wgs_opt < 0) c->wgs = ((algo >= 2) && (c->m[0].stream != c->m[1].stream) && gamma >= 6) ? SPEC_PEARL_WGS_PER_CU : 2;
@@ -839,7 +874,6 @@ extern "C" int spec_generate(spec_ctx* c, int algo, int gamma, int n_generate, i
   HIPCHK(hipStreamSynchronize(c->m[0].stream));
   HIPCHK(hipStreamSynchronize(c->m[1].stream));
   auto t1 = std::chrono::steady_clock::now();
-  c->wgs = wgs_before;
   for (int i = 0; i < n_generate && i < produced; ++i) out_tokens[i] = c->committed[base + i];
   if (stats) {
     stats[0] = (double)steps;
@@ -851,6 +885,127 @@ extern "C" int spec_generate(spec_ctx* c, int algo, int gamma, int n_generate, i
     stats[6] = (double)post_steps;
     stats[7] = std::chrono::duration<double>(t1 - t0).count();
   }
+  return SPEC_OK;
+}
+
+// Window size gamma = round(c), c = T(target forward) / T(draft forward) (Section 4.4.1).
+extern "C" int spec_calibrate_gamma(spec_ctx* c, int n_iter, int cap, int concurrent, int* gamma_out,
+                                    double* t_target_s, double* t_draft_s) {
+  if (!c || !gamma_out || !t_target_s || !t_draft_s) FAIL(SPEC_E_INVAL, "null argument");
+  if (n_iter < 1 || cap < 1) FAIL(SPEC_E_INVAL, "n_iter and cap must be positive");
+  if (!c->prefilled) FAIL(SPEC_E_STATE, "spec_prefill has not run");
+  if (c->n_drafted > 0 || c->last_verify_rows > 0)
+    FAIL(SPEC_E_STATE, "calibration needs a context between steps with no drafts pending");
+  ModelRt &mt = c->m[SPEC_TARGET], &md = c->m[SPEC_DRAFT];
+  if (mt.len != (int)c->committed.size() - 1 || md.len > (int)c->committed.size() - 1)
+    FAIL(SPEC_E_STATE, "caches do not match the committed tokens");
+  const int lt = mt.len, ld = md.len;
+  int rc = SPEC_OK;
+  // the forwards of the timed runs append to the caches: never more than fits
+  const int room_t = mt.n_pages * SPEC_PAGE_TOKENS - lt, room_d = md.n_pages * SPEC_PAGE_TOKENS - (int)c->committed.size();
+  int nt = n_iter < room_t ? n_iter : room_t;
+  int nd = n_iter < c->ring_n ? n_iter : c->ring_n;
+  if (nd > room_d) nd = room_d;
+  if (nt < 1 || nd < 1) FAIL(SPEC_E_NOMEM, "no room in the caches for a timed forward");
+  struct WgsGuard {
+    spec_ctx* c;
+    int saved;
+    ~WgsGuard() { c->wgs = saved; }
+  } wgs_guard{c, c->wgs};
+  if (concurrent && c->wgs_opt < 0) c->wgs = SPEC_PEARL_WGS_PER_CU;
+  TokenSrc src;
+  src.n = 1;
+  src.imm[0] = c->committed.back();
+  src.slot[0] = 0;
+  auto restore = [&]() -> int {   // leave caches, ring and mode as they were found
+    int r2;
+    HIPCHK(hipStreamSynchronize(mt.stream));
+    HIPCHK(hipStreamSynchronize(md.stream));
+    reset_ring(c);
+    c->last_verify_rows = 0;
+    if ((r2 = rollback_model(c, SPEC_TARGET, lt))) return r2;
+    if ((r2 = rollback_model(c, SPEC_DRAFT, ld))) return r2;
+    HIPCHK(hipStreamSynchronize(mt.stream));
+    HIPCHK(hipStreamSynchronize(md.stream));
+    return SPEC_OK;
+  };
+  auto fail = [&](int code) {
+    (void)restore();
+    return code;
+  };
+  // untimed: the first forward of a shape also captures its graphs
+  if ((rc = forward(c, SPEC_TARGET, src, 1))) return fail(rc);
+  if ((rc = spec_draft_step(c, 0.5f, nullptr))) return fail(rc);
+  if ((rc = restore())) return rc;
+  using clk = std::chrono::steady_clock;
+  double tp = 0.0, tq = 0.0;
+  if (!concurrent) {
+    auto t0 = clk::now();
+    for (int i = 0; i < nt; ++i)
+      if ((rc = forward(c, SPEC_TARGET, src, 1))) return fail(rc);
+    HIPCHK(hipStreamSynchronize(mt.stream));
+    tp = std::chrono::duration<double>(clk::now() - t0).count() / nt;
+    if ((rc = restore())) return rc;
+    t0 = clk::now();
+    for (int i = 0; i < nd; ++i)
+      if ((rc = spec_draft_step(c, 0.5f, nullptr))) return fail(rc);
+    HIPCHK(hipStreamSynchronize(md.stream));
+    tq = std::chrono::duration<double>(clk::now() - t0).count() / nd;
+  } else {
+    // Both streams busy at once, as inside a PEARL step: A target forwards beside B draft steps, B chosen from a
+    // first round so that the two chains end about together; each chain's time per forward is taken from its own
+    // start and end events.
+    if (mt.stream == md.stream) return fail((spec_set_error("concurrent calibration needs two streams"), SPEC_E_STATE));
+    hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
+    auto destroy = [&]() {
+      for (hipEvent_t& e : ev)
+        if (e) (void)hipEventDestroy(e), e = nullptr;
+    };
+    for (hipEvent_t& e : ev)
+      if (hipEventCreate(&e) != hipSuccess) {
+        destroy();
+        return fail((spec_set_error("hipEventCreate failed"), SPEC_E_HIP));
+      }
+    int A = 1, B = nd < 4 ? nd : 4;
+    for (int round = 0; round < 2; ++round) {
+      hipError_t e = hipEventRecord(ev[0], mt.stream);
+      if (e == hipSuccess) e = hipEventRecord(ev[2], md.stream);
+      for (int i = 0; i < A && !rc && e == hipSuccess; ++i) rc = forward(c, SPEC_TARGET, src, 1);
+      for (int i = 0; i < B && !rc && e == hipSuccess; ++i) rc = spec_draft_step(c, 0.5f, nullptr);
+      if (e == hipSuccess && !rc) e = hipEventRecord(ev[1], mt.stream);
+      if (e == hipSuccess && !rc) e = hipEventRecord(ev[3], md.stream);
+      if (e == hipSuccess && !rc) e = hipEventSynchronize(ev[1]);
+      if (e == hipSuccess && !rc) e = hipEventSynchronize(ev[3]);
+      float ms_t = 0.f, ms_d = 0.f;
+      if (e == hipSuccess && !rc) e = hipEventElapsedTime(&ms_t, ev[0], ev[1]);
+      if (e == hipSuccess && !rc) e = hipEventElapsedTime(&ms_d, ev[2], ev[3]);
+      if (rc || e != hipSuccess) {
+        destroy();
+        if (!rc) spec_set_error("concurrent calibration failed: %s", hipGetErrorString(e)), rc = SPEC_E_HIP;
+        return fail(rc);
+      }
+      tp = ms_t * 1e-3 / A;
+      tq = ms_d * 1e-3 / B;
+      if ((rc = restore())) {
+        destroy();
+        return rc;
+      }
+      // second round: two target forwards beside as many draft steps as take about the same time
+      A = nt < 2 ? nt : 2;
+      long long want = (long long)(A * tp / (tq > 0 ? tq : 1e-9) + 0.5);
+      B = (int)(want < 1 ? 1 : (want > nd ? nd : want));
+    }
+    destroy();
+  }
+  if ((rc = restore())) return rc;
+  double cc = tq > 0 ? tp / tq : (double)cap;
+  int g = (int)(cc + 0.5);
+  if (g < 1) g = 1;
+  if (g > cap) g = cap;
+  if (g > c->cfg.gamma_max) g = c->cfg.gamma_max;
+  *gamma_out = g;
+  *t_target_s = tp;
+  *t_draft_s = tq;
   return SPEC_OK;
 }
 
@@ -979,6 +1134,22 @@ extern "C" int spec_set_option(spec_ctx* c, int option, int value) {
     if (value < -1 || value > 1) FAIL(SPEC_E_INVAL, "SPEC_OPT_PREFILL takes -1, 0 or 1");
     c->prefill_opt = value;
     return SPEC_OK;
+  }
+  if (option == SPEC_OPT_TEST_FAIL_PREFILL) {
+    if (value < 0) FAIL(SPEC_E_INVAL, "SPEC_OPT_TEST_FAIL_PREFILL takes a count >= 0");
+    c->fail_prefill_after = value;
+    return SPEC_OK;
+  }
+  FAIL(SPEC_E_INVAL, "unknown option %d", option);
+}
+
+extern "C" int spec_get_option(const spec_ctx* c, int option, int* value) {
+  if (!c || !value) FAIL(SPEC_E_INVAL, "null argument");
+  switch (option) {
+    case SPEC_OPT_GEMM_WGS_PER_CU: *value = c->wgs; return SPEC_OK;       // what the next forward launches with
+    case SPEC_OPT_GRAPHS: *value = c->use_graphs ? 1 : 0; return SPEC_OK;
+    case SPEC_OPT_PREFILL: *value = c->prefill_opt; return SPEC_OK;
+    case SPEC_OPT_TEST_FAIL_PREFILL: *value = c->fail_prefill_after; return SPEC_OK;
   }
   FAIL(SPEC_E_INVAL, "unknown option %d", option);
 }

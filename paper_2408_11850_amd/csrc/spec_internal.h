@@ -14,7 +14,9 @@ typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 
 #define SPEC_PAGE_TOKENS 64      // tokens per KV page
 #define SPEC_RING_MAX 64         // most slots of the draft-token / q-row ring
-#define SPEC_NUM_CU 256
+// Compute units of the device the library runs on: 256 (MI355X) until spec_init has asked the device.
+int spec_num_cu();
+void spec_set_num_cu(int n);
 #define SPEC_PEARL_WGS_PER_CU 1   // projection workgroups per CU and stream while draft and target overlap
 
 // ---------------------------------------------------------------------------------------

@@ -169,6 +169,44 @@ def test_error_paths_leave_state_intact():
     ctx.close()
 
 
+@pytest.mark.parametrize("prefill_mode", [0, 1], ids=["chunked", "dense"])
+def test_prefill_that_fails_half_way_leaves_no_usable_looking_context(prefill_mode):
+    """A prompt pass that gives up after some of its forwards (forced from the host, as if the KV pages had run out)
+    has already reset the caches: every decoding call must then refuse with SPEC_E_STATE until a prefill succeeds.
+    Errors found before anything is touched leave the context usable."""
+    cfg = CASES["gqa64"]()
+    amd, ctx, tm, dm = _setup(cfg, gamma_max=4)
+    prompt = synth.prompt_tokens(150, cfg.target.vocab, 1).tolist()
+    ctx.set_option(amd.SPEC_OPT_PREFILL, prefill_mode)
+    ctx.prefill(prompt)
+    ref = ctx.verify([prompt[-1], 5, 9], want_logits=True)
+    ctx.rewind(len(prompt))
+    # refused before anything is touched: the context stays as it was
+    with pytest.raises(amd.SpecError) as e:
+        ctx.prefill(list(range(1000)) * 3)                              # cannot fit max_seq
+    assert e.value.code == amd.SPEC_E_NOMEM
+    with pytest.raises(amd.SpecError) as e:
+        ctx.prefill(prompt[:10] + [cfg.target.vocab])                   # token outside the vocabulary
+    assert e.value.code == amd.SPEC_E_INVAL
+    assert np.array_equal(ctx.verify([prompt[-1], 5, 9], want_logits=True), ref)
+    ctx.rewind(len(prompt))
+    # gives up half way
+    ctx.set_option(amd.SPEC_OPT_TEST_FAIL_PREFILL, 1 if prefill_mode else 2)
+    with pytest.raises(amd.SpecError) as e:
+        ctx.prefill(prompt)
+    assert e.value.code == amd.SPEC_E_NOMEM
+    for call in (lambda: ctx.verify([1]), lambda: ctx.draft_step(0.5), lambda: ctx.rewind(1),
+                 lambda: ctx.calibrate_gamma(2, 4),
+                 lambda: ctx.generate(amd.ALGO_AR, 1, 2, NpUniforms(synth.make_uniforms(4, 1, 3)))):
+        with pytest.raises(amd.SpecError) as e:
+            call()
+        assert e.value.code == amd.SPEC_E_STATE
+    assert ctx.get_option(amd.SPEC_OPT_TEST_FAIL_PREFILL) == 0          # one-shot
+    ctx.prefill(prompt)
+    assert np.array_equal(ctx.verify([prompt[-1], 5, 9], want_logits=True), ref)
+    ctx.close()
+
+
 def test_graph_replays_equal_kernel_by_kernel_launches():
     """Captured forwards (HIP graphs) are replayed several times, with eager forwards, rollbacks and
     synchronisations in between; every replay must equal the kernel-by-kernel result bit for bit."""

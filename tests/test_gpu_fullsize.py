@@ -14,7 +14,7 @@ import torch
 
 import synth
 from oracle import transformer
-from tests.util import gpu_available, oracle_model
+from tests.util import gpu_available, np_weights as np_weights_of, oracle_model
 
 pytestmark = [pytest.mark.gpu, pytest.mark.skipif(not gpu_available(), reason="needs a GPU")]
 
@@ -73,69 +73,185 @@ def test_full_width_truncated_pair_matches_oracle(name, prefill_mode):
     ctx.close()
 
 
-@pytest.mark.parametrize("name", ["70b_7b", "33b_1b"])
-def test_full_width_truncated_pair_decodes_like_the_oracle(name):
-    """PEARL (gamma 4) on the real widths and the real vocabulary (depth cut as above), step by step against the
-    oracle: draws over 32000 ids and residual resampling on full-size rows, pre- and post-verify bookkeeping.  A random-init net of
-    this depth spreads its mass over thousands of tokens at temperature 1 (every step then holds a draw within
-    1e-4 of a CDF edge), so the comparison runs at a temperature that makes the distributions as peaked as a
-    trained model's."""
+def _cpu_weights(w):
+    return {"tok_embed": w["tok_embed"].cpu(), "lm_head": w["lm_head"].cpu(), "final_norm": w["final_norm"].cpu(),
+            "layers": [{k: v.cpu() for k, v in lay.items()} for lay in w["layers"]]}
+
+
+@pytest.mark.parametrize("name,self_draft", [("70b_7b", False), ("70b_7b", True), ("33b_1b", False)],
+                         ids=["70b_7b", "70b_first_layer_as_draft", "33b_1b"])
+def test_full_width_truncated_pair_decodes_like_the_oracle(name, self_draft):
+    """PEARL and SD (gamma 4, temperature 1, the pair's own accept / reject decisions) on the real widths and the real
+    vocabulary, depth cut to 2 target layers so that the fp32 oracle can hold the pair: every forward of the run
+    against the oracle forward (2e-2 of the row's range), every committed token against the oracle's loop on the
+    library's logits - draws over 32000 ids, acceptance ratios and residual resampling on model-produced rows.
+    With an independent random-init draft the acceptance rate is what chance gives; with the target's own first layer
+    as the draft model (shared embedding and LM head) it lies in the range trained pairs show."""
     import paper_2408_11850_amd as amd
     from paper_2408_11850_amd import harness
-    from oracle import loops
-    from tests.util import NpUniforms
-    from tests.test_gpu_loops import MARGIN_TOL, _gpu_steps
+    from tests.test_gpu_loops import lockstep_run
+    from tests.util import EXACT_MARGIN
     cfg = synth.config(name, depth=2, draft_depth=1)
+    if self_draft:
+        cfg.draft_from_target_layers = 1
+        cfg.draft = synth._truncate(cfg.target, 1)
     tw, dw = synth.make_pair(cfg, device="cuda")
     target, draft = harness.build_pair(cfg, weights=(tw, dw))
-    cpu = lambda w: {"tok_embed": w["tok_embed"].cpu(), "lm_head": w["lm_head"].cpu(), "final_norm": w["final_norm"].cpu(),
-                     "layers": [{k: v.cpu() for k, v in lay.items()} for lay in w["layers"]]}
-    tm = oracle_model(cpu(tw), cfg.target)
-    dm = oracle_model(cpu(dw), cfg.draft)
+    tm = oracle_model(_cpu_weights(tw), cfg.target)
+    dm = oracle_model(_cpu_weights(dw), cfg.draft)
     del tw, dw
     cfg.n_prompt, cfg.n_generate = 100, 64
-    gamma, seg_len, n_total, temperature = 4, 12, 36, 0.02
-    # At this temperature the logits are multiplied by 50, and so is the bf16 path's logit error (up to 8e-3 of a
-    # logit range of about 1): a CDF edge or an acceptance ratio can move by up to 0.25 * 50 * 8e-3 = 0.1, so a
-    # split is tolerated on a step whose smallest oracle margin is below that; both sides then restart from the
-    # oracle's tokens, and splits must stay the exception.
-    margin_tol = 0.1
     prompt = synth.prompt_tokens(cfg.n_prompt, cfg.target.vocab, 9).tolist()
-    ctx = harness.make_context(cfg, target, draft, 8, temperature=temperature, extra_seq=n_total + 32)
-    # an independent random-init draft never agrees with the target, so the accept / reject pattern is scripted
-    # (both sides take the same decisions; what is compared are the tokens: draft draws, corrected tokens from
-    # the residual of full-size rows, and the bookkeeping of both modes)
-    force = lambda t, i: not ((t % 4 == 1 and i == 2) or (t % 5 == 2 and i == 0))
-    done, segments, splits, agreed, modes, full_accepts = 0, 0, 0, 0, set(), 0
-    while done < n_total:
-        uni = NpUniforms(synth.make_uniforms(seg_len + 1, gamma, 31 + segments))
-        print(f"{name}: segment {segments}, prompt of {len(prompt)} tokens", flush=True)
-        ref = []
-        mk = lambda m: transformer.CachedModel(m, len(prompt) + seg_len + 4 * gamma + 8)
-        loops.pearl(mk(tm), mk(dm), prompt, seg_len, gamma, uni, temperature=temperature, logit_scale=cfg.logit_scale,
-                    force=force, trace=ref)
-        ctx.prefill(prompt)
-        got = _gpu_steps(amd, ctx, amd.ALGO_PEARL, gamma, seg_len, uni, force=force)
-        k = 0
-        while k < min(len(ref), len(got)) and ref[k]["tokens"] == got[k]["tokens"]:
-            modes.add(ref[k]["mode"])
-            full_accepts += ref[k]["n_accepted"] == gamma
-            k += 1
-        agreed += k
-        committed = [t for r in ref[:k] for t in r["tokens"]]
-        if k < min(len(ref), len(got)):
-            print(f"  split at step {k}: oracle margin {ref[k]['margin']:.4f}", flush=True)
-            assert ref[k]["margin"] < margin_tol, (k, ref[k], got[k])
-            committed += ref[k]["tokens"]
-            splits += 1
-        prompt = prompt + committed
-        done += len(committed)
-        segments += 1
-        assert segments < 20
-    print(f"  {agreed} steps agreed, {splits} sub-margin splits", flush=True)
-    assert agreed >= 3 * max(1, splits)
-    assert modes >= {loops.PRE, loops.POST} and full_accepts >= 1
+    for algo in (amd.ALGO_PEARL, amd.ALGO_SD):
+        print(f"{name} self_draft={self_draft} algo={algo}", flush=True)
+        agreed, splits, wt, wd, modes = lockstep_run(amd, harness, cfg, target, draft, tm, dm, algo, 4, 1.0,
+                                                     n_total=40, seed=31, prompt=prompt, first_segment=40)
+        print(f"  {agreed} steps identical, {splits} splits within {EXACT_MARGIN} of a flip; worst logit error "
+              f"target {wt:.2e} draft {wd:.2e}; modes {sorted(map(str, modes))}", flush=True)
+        assert splits <= 2 and agreed >= 8 * max(1, splits)
+        if self_draft and algo == amd.ALGO_PEARL:
+            assert modes >= {"pre-verify", "post-verify"}
+
+
+@pytest.fixture(scope="module")
+def small_pair_full_depth():
+    """The small pair at its full depth (24 target layers of width 2048, draft = its first 4 layers, vocab 32000),
+    the oracle in fp32 (5.4 GB), and the oracle's caches after the 512-token prompt."""
+    import paper_2408_11850_amd as amd
+    from paper_2408_11850_amd import harness
+    cfg = synth.config("small")
+    print("small pair at full depth: weights", flush=True)
+    tw, dw = synth.make_pair(cfg, device="cuda")
+    target, draft = harness.build_pair(cfg, weights=(tw, dw))
+    tm = oracle_model(_cpu_weights(tw), cfg.target)
+    dm = oracle_model(_cpu_weights(dw), cfg.draft)
+    del tw, dw
+    prompt = synth.prompt_tokens(cfg.n_prompt, cfg.target.vocab, cfg.seed_prompt).tolist()
+    print("small pair at full depth: oracle prompt pass (511 tokens, 24 + 4 layers)", flush=True)
+    caches = []
+    for m in (tm, dm):
+        c = transformer.CachedModel(m, cfg.n_prompt + 160)
+        c.feed(prompt[:-1])
+        caches.append(c)
+    return amd, harness, cfg, target, draft, tm, dm, prompt, caches
+
+
+def _copy_cache(c):
+    """A second oracle cache with the same contents (the weights are shared, not copied)."""
+    n = transformer.CachedModel(c.model, c.cache.k.shape[1])
+    n.cache.k[:, :c.len] = c.cache.k[:, :c.len]
+    n.cache.v[:, :c.len] = c.cache.v[:, :c.len]
+    n.cache.len = c.len
+    return n
+
+
+@pytest.mark.parametrize("prefill_mode", [1, 0], ids=["dense_prefill", "chunked_prefill"])
+def test_small_pair_at_full_depth_verify_rows_match_the_oracle(small_pair_full_depth, prefill_mode):
+    """24 layers deep, behind the 512-token prompt (either prompt path): verify forwards of 1, 5 and 9 rows."""
+    amd, harness, cfg, target, draft, tm, dm, prompt, _ = small_pair_full_depth
+    ctx = harness.make_context(cfg, target, draft, 8, extra_seq=64)
+    ctx.set_option(amd.SPEC_OPT_PREFILL, prefill_mode)
+    ctx.prefill(prompt)
+    oc = _copy_cache(small_pair_full_depth[8][0])
+    extra = synth.prompt_tokens(16, cfg.target.vocab, 8).tolist()
+    worst, pos = 0.0, 0
+    for m in (1, 5, 9):
+        toks = ([prompt[-1]] + extra)[pos:pos + m]
+        pos += m
+        got = ctx.verify(toks, want_logits=True)
+        ref = oc.feed(toks)
+        worst = max(worst, _rel_err(got, ref))
+        print(f"  24 layers, M={m}: logit error / range so far {worst:.2e}", flush=True)
     ctx.close()
+    assert worst <= 2e-2
+
+
+# (algo, gamma, temperature, prompt path): the workload's own settings (greedy and temperature 1, windows 4 and 8), and
+# temperature 0.3, where the distributions are as peaked as a trained model's
+SMALL_FULL_DEPTH_CASES = [(1, 4, 0.3, 1), (2, 4, 0.3, 1), (2, 4, 0.3, 0), (2, 8, 0.0, 1), (1, 8, 0.0, 0), (1, 4, 1.0, 1),
+                          (2, 8, 1.0, 1)]
+
+
+@pytest.mark.parametrize("algo,gamma,temperature,prefill_mode", SMALL_FULL_DEPTH_CASES)
+def test_small_pair_at_full_depth_decodes_like_the_oracle(small_pair_full_depth, algo, gamma, temperature, prefill_mode):
+    """SD / PEARL with the pair's own decisions at the full 24-layer depth behind the 512-token prompt: every target
+    forward (1, gamma and gamma + 1 rows) and every draft forward against the fp32 oracle, every committed token
+    against the oracle's loop on the library's logits.  At temperature 1 this random-init pair spreads its mass
+    almost evenly over the 32000 ids: CDF edges lie 3e-5 apart, every draw sits within 2e-5 of one, and the last
+    bits of exp() already move a few per cent of the draws to a neighbouring id - there the test can only demand
+    that each split is such a close call; greedy runs must agree token for token, and at temperature 0.3 splits must
+    be rare."""
+    from tests.test_gpu_loops import lockstep_run
+    from tests.util import EXACT_MARGIN
+    amd, harness, cfg, target, draft, tm, dm, prompt, filled = small_pair_full_depth
+    caches = (_copy_cache(filled[0]), _copy_cache(filled[1]))
+    n_total = 40 if temperature == 1.0 else 96
+    agreed, splits, wt, wd, modes = lockstep_run(amd, harness, cfg, target, draft, tm, dm, algo, gamma, temperature,
+                                                 n_total=n_total, seed=cfg.seed_uniform, prompt=prompt,
+                                                 prefill_mode=prefill_mode, first_segment=n_total, oracle_caches=caches)
+    print(f"algo={algo} gamma={gamma} T={temperature} prefill={prefill_mode}: {agreed} steps identical, {splits} splits "
+          f"within {EXACT_MARGIN} of a flip; worst logit error target {wt:.2e} draft {wd:.2e}", flush=True)
+    if temperature == 0.0:
+        assert splits == 0 and agreed >= 10
+    elif temperature < 1.0:
+        assert splits <= 1 and agreed >= 24
+    else:
+        assert agreed >= 12
+
+
+DEPTH_TOL_FP32 = {2: 2e-2, 4: 2e-2, 8: 4e-2}    # against the fp32 oracle: the stated 2e-2 holds up to 4 layers at these widths
+DEPTH_TOL_BF16 = 2e-2                              # against the oracle with bf16 activations, any depth measured
+
+
+def test_logit_error_against_the_oracle_as_depth_grows_at_70b_widths():
+    """The 70B-shape target at 2, 4 and 8 layers (the deeper models share the shallower ones' layers) against the
+    oracle: verify forwards of 1 and 7 rows behind a 150-token prompt.  Three distances per depth: library vs fp32
+    oracle, library vs the oracle with bf16 activations (the same rounding points as a bf16 deployment), and the two
+    oracles against each other.  In a random-init network a perturbation grows from layer to layer, so bf16
+    activations alone (oracle vs oracle, no library involved) leave the 2e-2 of the fp32 logits' range behind at
+    about 8 layers of these widths; the library must stay as close to the fp32 oracle as the bf16-activation oracle
+    does (within a factor), and closer to that oracle than to the fp32 one."""
+    import paper_2408_11850_amd as amd
+    from paper_2408_11850_amd import harness
+    cfg = synth.config("70b_7b", depth=8, draft_depth=1)
+    print("70B widths, 8 layers: generating weights on the GPU", flush=True)
+    tw, dw = synth.make_pair(cfg, device="cuda")
+    target8, draft = harness.build_pair(cfg, weights=(tw, dw))
+    w8 = np_weights_of(_cpu_weights(tw))
+    del tw, dw
+    cfg.n_prompt, cfg.n_generate = 150, 32
+    prompt = synth.prompt_tokens(cfg.n_prompt, cfg.target.vocab, 7).tolist()
+    extra = synth.prompt_tokens(8, cfg.target.vocab, 8).tolist()
+    curve = {}
+    for depth in (2, 4, 8):
+        shape = synth._truncate(cfg.target, depth)
+        tgt = target8.prefix(depth, shape)
+        cfg_k = synth.config("70b_7b", depth=depth, draft_depth=1)
+        cfg_k.n_prompt, cfg_k.n_generate = cfg.n_prompt, cfg.n_generate
+        ctx = harness.make_context(cfg_k, tgt, draft, 8)
+        ctx.set_option(amd.SPEC_OPT_PREFILL, 0)      # the prompt through the same kernels as the verify forwards
+        ctx.prefill(prompt)
+        wk = dict(w8, layers=w8["layers"][:depth])
+        mk = lambda r: transformer.CachedModel(transformer.Model(wk, shape.n_heads, shape.n_kv_heads, shape.head_dim,
+                                                                 shape.rope_theta, shape.rms_eps, act_bf16=r), 256)
+        o32, o16 = mk(False), mk(True)
+        print(f"  depth {depth}: oracle prompt passes", flush=True)
+        o32.feed(prompt[:-1])
+        o16.feed(prompt[:-1])
+        e32 = e16 = eoo = 0.0
+        for toks in ([prompt[-1]], extra[:7]):
+            got = ctx.verify(toks, want_logits=True)
+            r32, r16 = o32.feed(toks), o16.feed(toks)
+            e32, e16, eoo = max(e32, _rel_err(got, r32)), max(e16, _rel_err(got, r16)), max(eoo, _rel_err(r16, r32))
+        ctx.close()
+        curve[depth] = (e32, e16, eoo)
+        print(f"  depth {depth}: library vs fp32 oracle {e32:.2e}, library vs bf16-activation oracle {e16:.2e}, "
+              f"bf16-activation oracle vs fp32 oracle {eoo:.2e} (max |dlogit| / row range)", flush=True)
+    print(f"depth curve at 70B widths: {curve}", flush=True)
+    for depth, (e32, e16, eoo) in curve.items():
+        assert e32 <= DEPTH_TOL_FP32[depth], (depth, e32)
+        assert e32 <= 1.5 * eoo + 2e-3, (depth, e32, eoo)     # no further from fp32 than bf16 activations put anyone
+        assert e16 <= DEPTH_TOL_BF16 and e16 <= 0.75 * e32 + 1e-3, (depth, e16, e32)   # measured: about half of e32
 
 
 def test_full_depth_pair_properties_in_benchmark_configuration():
