@@ -243,6 +243,18 @@ int spec_accept_rows(const float* p_logits_dev, int n_rows, const float* q_rows_
                      int n_test, int vocab, float temperature, float logit_scale, const float* r_host,
                      float u_resample, int32_t* result_host, void* stream);
 
+/* spec_accept_rows for callers that cannot allocate (code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc): same arguments and the same kernels, but the kernels' scratch (row statistics, one row
+ * of draw weights, the result record) lives in a device array of the library, about 1 MiB that every GPU the
+ * library runs on holds until the process ends, and the outcome goes to result_dev[0..1] (device memory of the
+ * caller: n_accepted, corrected / bonus token or -1).  Calls no hipMalloc / hipFree; asynchronous on `stream`.
+ * vocab <= SPEC_STATIC_VOCAB_MAX, else SPEC_E_INVAL.  All calls on one GPU share the array: calls that overlap on
+ * one GPU (two streams, two threads) race - serialise them. */
+#define SPEC_STATIC_VOCAB_MAX 262144
+int spec_accept_rows_static(const float* p_logits_dev, int n_rows, const float* q_rows_dev, const int32_t* x_dev,
+                            int n_test, int vocab, float temperature, float logit_scale, const float* r_host,
+                            float u_resample, int32_t* result_dev, void* stream);
+
 /* Options.  SPEC_OPT_GEMM_WGS_PER_CU: how many workgroups of a projection kernel are launched per compute
  * unit.  2 fills both slots of every CU (fastest when a stream runs alone), 1 leaves one slot to the other
  * stream's kernels so that draft and target passes run side by side, -1 (default) = automatic: spec_generate's

@@ -82,6 +82,8 @@ SIGNATURES = {
     "spec_sample_row": (C.c_int, [_P, C.c_int, C.c_float, C.c_float, C.c_float, _P, _P, _P]),
     "spec_accept_rows": (C.c_int, [_P, C.c_int, _P, _P, C.c_int, C.c_int, C.c_float, C.c_float, _PF, C.c_float,
                                    _PI32, _P]),
+    "spec_accept_rows_static": (C.c_int, [_P, C.c_int, _P, _P, C.c_int, C.c_int, C.c_float, C.c_float, _PF, C.c_float,
+                                          _P, _P]),
     "spec_set_option": (C.c_int, [_P, C.c_int, C.c_int]),
     "spec_get_option": (C.c_int, [_P, C.c_int, _PI]),
     "spec_set_profile": (C.c_int, [_P, C.c_int]),
@@ -119,4 +121,4 @@ def check(rc: int) -> int:
     return rc
 
 
-from .binding import SpecContext, pack_model, gemm, dense_gemm, sample_row, accept_rows, read_probe  # noqa: E402,F401
+from .binding import SpecContext, pack_model, gemm, dense_gemm, sample_row, accept_rows, accept_rows_static, read_probe  # noqa: E402,F401

@@ -347,6 +347,22 @@ def accept_rows(p_logits: torch.Tensor, q_rows: Optional[torch.Tensor], x, r, te
     return res[0], res[1]
 
 
+def accept_rows_static(p_logits: torch.Tensor, q_rows: Optional[torch.Tensor], x: Optional[torch.Tensor], r,
+                       temperature: float, logit_scale: float, u_resample: float, result: torch.Tensor):
+    """spec_accept_rows_static on torch's current stream: allocates nothing (x and result are the caller's device
+    tensors: int32 [n_test] and int32 [2]); asynchronous."""
+    lib = load_library()
+    assert p_logits.dtype == torch.float32 and p_logits.is_contiguous()
+    assert result.dtype == torch.int32 and result.numel() >= 2 and result.is_cuda
+    n_rows, V = p_logits.shape
+    n_test = 0 if x is None else int(x.numel())
+    rr = np.ascontiguousarray(np.asarray(r, dtype=np.float32))
+    check(lib.spec_accept_rows_static(_ptr(p_logits), n_rows, _ptr(q_rows) if n_test else None,
+                                      _ptr(x) if n_test else None, n_test, V, float(temperature), float(logit_scale),
+                                      rr.ctypes.data_as(C.POINTER(C.c_float)), float(u_resample), _ptr(result),
+                                      _stream_ptr(torch.cuda.current_stream())))
+
+
 def read_probe(buf: torch.Tensor):
     lib = load_library()
     out = torch.zeros(4, dtype=torch.int32, device=buf.device)

@@ -8,6 +8,8 @@
 // One workgroup of 1024 threads handles one vocabulary row.  With a single compute unit per row the kernels are
 // bound by its vector ALU and by the latency of dependent passes, so rows of up to 32768 ids are held in
 // registers and read once (the reg_* functions); longer rows take the generic multi-pass kernels.
+#include <cstring>
+
 #include "spec_internal.h"
 
 #define SAMP_THREADS 1024
@@ -381,7 +383,8 @@ __global__ __launch_bounds__(SAMP_THREADS) void accept_finish_kernel(const float
                                                                      const int* __restrict__ x_direct, AcceptArgs a,
                                                                      const float* __restrict__ stats,
                                                                      float* __restrict__ wbuf,
-                                                                     AcceptResult* __restrict__ res) {
+                                                                     AcceptResult* __restrict__ res,
+                                                                     int* __restrict__ out2) {
   __shared__ double shd[SAMP_WAVES];
   __shared__ int shi[2];
   __shared__ double rt[SAMP_WAVES][SAMP_ROWS_MAX + 1];
@@ -448,19 +451,110 @@ __global__ __launch_bounds__(SAMP_THREADS) void accept_finish_kernel(const float
     res->token = token;
     res->rejected = rejected ? 1 : 0;
     res->pad = 0;
+    if (out2) {   // callers that want the outcome in device memory of their own
+      out2[0] = n;
+      out2[1] = token;
+    }
   }
   if (ring && threadIdx.x < SPEC_RING_MAX) res->ring[threadIdx.x] = ring[threadIdx.x];
 }
 
 hipError_t launch_accept(const float* logits, int V, float mult, int greedy, const float* qcache, const int* ring,
                          const int* x_direct, AcceptArgs a, float* stats_scratch, AcceptResult* result_dev,
-                         hipStream_t st) {
+                         hipStream_t st, int* out2) {
   // stats_scratch: 4 floats per row, followed (at a 256-float offset) by one scratch row of V floats
   accept_rows_kernel<<<a.n_rows, SAMP_THREADS, 0, st>>>(logits, V, mult, greedy, qcache, ring, x_direct, a,
                                                         stats_scratch);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   accept_finish_kernel<<<1, SAMP_THREADS, 0, st>>>(logits, V, mult, greedy, qcache, ring, x_direct, a, stats_scratch,
-                                                   stats_scratch + 256, result_dev);
+                                                   stats_scratch + 256, result_dev, out2);
   return hipGetLastError();
+}
+
+// ---- acceptance without any allocation ---------------------------------------------------------
+// The scratch of the two acceptance kernels (row statistics, one row of draw weights, the result record) in a
+// file-scope device array instead of memory from hipMalloc: for callers that must not allocate (code under HIP
+// graph capture, tight serving loops).  Every GPU the library runs on holds its own copy of the array until the
+// process ends; its address on a device is looked up once, with that device current.  All calls on one GPU share
+// the array, so calls that overlap on one GPU (two streams, two threads) race; nothing in it has to start at zero
+// (every word a call reads was written by that call before).
+#define ACCEPT_STATIC_STATS_FLOATS 256
+#define ACCEPT_STATIC_BYTES ((ACCEPT_STATIC_STATS_FLOATS + SPEC_STATIC_VOCAB_MAX) * 4 + 512)
+static __device__ __align__(256) unsigned char scratch[ACCEPT_STATIC_BYTES];
+
+#include <mutex>
+#define ACCEPT_STATIC_MAX_DEVICES 64
+static void* g_scratch_ptr[ACCEPT_STATIC_MAX_DEVICES];
+static std::mutex g_scratch_mutex;
+
+// device address of `scratch` on the current device (nullptr and an error message on failure)
+static void* static_scratch_ptr() {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess || dev < 0 || dev >= ACCEPT_STATIC_MAX_DEVICES) {
+    spec_set_error("hipGetDevice failed or device id %d above %d: %s", dev, ACCEPT_STATIC_MAX_DEVICES - 1,
+                   hipGetErrorString(e));
+    return nullptr;
+  }
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) {
+      spec_set_error("hipGetSymbolAddress(scratch) failed on device %d: %s", dev, hipGetErrorString(e));
+      return nullptr;
+    }
+    g_scratch_ptr[dev] = p;
+  }
+  return g_scratch_ptr[dev];
+}
+
+extern "C" int spec_accept_rows_static(const float* p_logits, int n_rows, const float* q_rows, const int32_t* x,
+                                       int n_test, int vocab, float temperature, float logit_scale, const float* r,
+                                       float u_resample, int32_t* result_dev, void* stream) {
+  if (!p_logits || !result_dev || vocab < 1 || n_rows < 1 || n_rows > SPEC_MAX_TOKENS || n_test < 0 || n_test > n_rows) {
+    spec_set_error("bad argument");
+    return SPEC_E_INVAL;
+  }
+  if (vocab > SPEC_STATIC_VOCAB_MAX) {
+    spec_set_error("vocabulary of %d ids is above the %d the static scratch holds; use spec_accept_rows", vocab,
+                   SPEC_STATIC_VOCAB_MAX);
+    return SPEC_E_INVAL;
+  }
+  if (n_test > 0 && (!q_rows || !x || !r)) {
+    spec_set_error("null pointer");
+    return SPEC_E_INVAL;
+  }
+  if (!(temperature >= 0.0f) || !(logit_scale > 0.0f) || !(u_resample >= 0.0f && u_resample < 1.0f)) {
+    spec_set_error("bad temperature / logit_scale / uniform");
+    return SPEC_E_INVAL;
+  }
+  static_assert(4 * SPEC_MAX_TOKENS <= ACCEPT_STATIC_STATS_FLOATS, "four statistics per row");
+  static_assert(sizeof(AcceptResult) <= 512, "the result record sits in the last 512 bytes");
+  unsigned char* base = (unsigned char*)static_scratch_ptr();
+  if (!base) return SPEC_E_HIP;
+  AcceptArgs a;
+  memset(&a, 0, sizeof(a));
+  a.n_rows = n_rows;
+  a.n_test = n_test;
+  a.u_resample = u_resample;
+  a.force_mask = -1;
+  for (int i = 0; i < n_test; ++i) {
+    if (!(r[i] >= 0.0f && r[i] < 1.0f)) {
+      spec_set_error("uniform outside [0,1)");
+      return SPEC_E_INVAL;
+    }
+    a.r[i] = r[i];
+  }
+  const bool greedy = temperature == 0.0f;
+  float* stats = (float*)base;
+  AcceptResult* res = (AcceptResult*)(base + (size_t)(ACCEPT_STATIC_STATS_FLOATS + SPEC_STATIC_VOCAB_MAX) * 4);
+  hipError_t e = launch_accept(p_logits, vocab, greedy ? 1.0f : logit_scale / temperature, greedy ? 1 : 0, q_rows,
+                               nullptr, x, a, stats, res, (hipStream_t)stream, result_dev);
+  if (e != hipSuccess) {
+    spec_set_error("accept kernels failed to launch: %s", hipGetErrorString(e));
+    return SPEC_E_HIP;
+  }
+  return SPEC_OK;
 }

@@ -154,6 +154,6 @@ hipError_t launch_sample_row(const float* logits, int V, float mult, int greedy,
                              hipStream_t st);
 hipError_t launch_accept(const float* logits, int V, float mult, int greedy, const float* qcache, const int* ring,
                          const int* x_direct, AcceptArgs a, float* stats_scratch, AcceptResult* result_dev,
-                         hipStream_t st);
+                         hipStream_t st, int* out2 = nullptr);
 
 void spec_set_error(const char* fmt, ...);
