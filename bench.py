@@ -39,6 +39,15 @@ def parse():
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the benchmark line: tokens/s of PEARL and SD over window sizes and acceptance rates")
     ap.add_argument("--sweep-part", default="all", help="with --sweep: all | gamma | cu (which part of the study to run)")
+    ap.add_argument("--phase", default="", choices=["", "verify", "verify-graph", "draft"],
+                    help="run only that pass alone (N = --steps forwards at the prompt's context length) and print its "
+                         "figures: verify = kernel by kernel with an event pair per projection launch, verify-graph / draft = "
+                         "captured graphs replayed; the commands the rocprofv3 summaries under profiles/ are made with")
+    ap.add_argument("--library-generator", action="store_true",
+                    help="weights of the same shapes and distributions from PyTorch's generator instead of the counter-based "
+                         "one: for runs under rocprofv3 --pmc, whose counter collection crashes on PyTorch's run-time-compiled "
+                         "inverse-normal kernel (kernel counters do not depend on the values)")
+    ap.add_argument("--fuse", type=int, default=-1, help="SPEC_OPT_FUSE_SINGLE value (experiments)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
     ap.add_argument("--no-side", action="store_true", help="skip AR / SD / forced-acceptance side runs")
     return ap.parse_args()
@@ -190,6 +199,55 @@ def sweep(args, cfg, ctx, amd, synth, sync, n0, tp, tq, log):
                       "ar_tokens_per_s": ar[0], "rows": rows, "cu_split_gamma": g, "cu_split": split_rows}))
 
 
+def phase(args, cfg, ctx, amd, sync, n0, gamma, log):
+    """One pass alone, N = --steps forwards at the prompt's context length; the commands behind the per-kernel tables
+    in profiles/ (run under `rocprofv3 --kernel-trace --stats` or `--pmc ...`, with --gamma given so that no
+    calibration forwards mix in).
+      verify        kernel by kernel, every projection launch stamping a HIP event pair with its own start / end:
+                    the dominant kernel's average launch duration as bench.py's roofline object measures it
+      verify-graph  the same forwards as the library runs them (captured graphs replayed): the pass's wall time
+      draft         draft forwards (with their draws), graphs replayed"""
+    N = max(1, args.steps)
+    verify = args.phase.startswith("verify")
+    shape = cfg.target if verify else cfg.draft
+    out = {"phase": args.phase, "workload": cfg.name, "n_ctx": n0 - 1, "forwards": N, "gamma": gamma}
+
+    def run_verify(m):
+        toks = list(range(1, m + 1))
+        for _ in range(N):
+            ctx.verify(toks)
+            ctx.rollback_kv(amd.SPEC_TARGET, n0 - 1)
+
+    def run_draft(_m):
+        done = 0
+        while done < N:                       # at most 2 * gamma_max drafts may be pending
+            k = min(N - done, 2 * ctx.gamma_max)
+            for _ in range(k):
+                ctx.draft_step(0.5)
+            ctx.rewind(n0)
+            done += k
+
+    for m in ((1, gamma) if verify else (1,)):
+        b = forward_bytes(shape, n0 - 1, m)
+        if args.phase == "verify":
+            ctx.set_profile(1); ctx.profile_read()
+            _, t = timed(lambda: run_verify(m), sync)
+            ms, n, by = ctx.profile_read()
+            ctx.set_profile(0)
+            out[f"m{m}"] = {"projection_kernel": {
+                "launches": int(n), "avg_launch_us": ms / max(n, 1) * 1e3, "avg_bytes_per_launch": by / max(n, 1),
+                "GBps": by / max(ms, 1e-9) / 1e6, "frac_of_peak": by / max(ms, 1e-9) / 1e6 / HBM_PEAK_GBS},
+                "forward_ms_kernel_by_kernel": t / N * 1e3}
+        else:
+            run = run_verify if verify else run_draft
+            run(m); sync()                        # captures the graphs of this shape
+            _, t = timed(lambda: run(m), sync)
+            out[f"m{m}"] = {"forward_ms": t / N * 1e3, "GBps": b / (t / N) / 1e9,
+                            "frac_of_peak": b / (t / N) / 1e9 / HBM_PEAK_GBS, "algorithmic_bytes": b}
+        log(f"[bench] phase {args.phase} M={m}: {json.dumps(out[f'm{m}'])}")
+    print(json.dumps(out))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -210,11 +268,13 @@ def main():
     gamma_max = 16
     log = lambda *a: print(*a, file=sys.stderr, flush=True)
 
-    (pair, t_build) = timed(lambda: harness.build_pair(cfg, dev), sync)
+    (pair, t_build) = timed(lambda: harness.build_pair(cfg, dev, library_generator=args.library_generator), sync)
     target, draft = pair
     log(f"[bench] built {cfg.name}: target {target.nbytes() / 1e9:.2f} GB, draft {draft.nbytes() / 1e9:.2f} GB in {t_build:.1f}s")
     ctx = harness.make_context(cfg, target, draft, gamma_max, extra_seq=64)
     ctx.set_option(amd.SPEC_OPT_GEMM_WGS_PER_CU, args.wgs)
+    if args.fuse >= 0:
+        ctx.set_option(amd.SPEC_OPT_FUSE_SINGLE, args.fuse)
     prompt = synth.prompt_tokens(cfg.n_prompt, cfg.target.vocab, cfg.seed_prompt).tolist()
     # prompt pass of each model alone (dense matrix-core path when the shapes allow it), then both for the run
     def prefill_flops(sh, c):
@@ -235,10 +295,23 @@ def main():
     n0 = cfg.n_prompt
 
     # ---- window size: gamma = round(c), c = T(target forward) / T(draft forward) ---------------
-    g_cal, tp, tq = harness.calibrate_gamma(ctx, n_iter=8, cap=gamma_max)
+    # (Section 4.4.1; the library measures it: each model with the GPU to itself, as on the paper's separate devices,
+    # and with both streams busy at once, as inside a PEARL step on one GPU)
+    if args.phase and args.gamma:
+        phase(args, cfg, ctx, amd, sync, n0, args.gamma, log)
+        ctx.close()
+        return
+    g_cal, tp, tq = ctx.calibrate_gamma(8, gamma_max, concurrent=False)
+    g_con, tp_c, tq_c = ctx.calibrate_gamma(8, gamma_max, concurrent=True)
     gamma = args.gamma or g_cal
-    log(f"[bench] target fwd {tp * 1e3:.2f} ms, draft fwd {tq * 1e3:.2f} ms, c = {tp / tq:.2f}, gamma = {gamma}")
+    log(f"[bench] alone: target fwd {tp * 1e3:.2f} ms, draft fwd {tq * 1e3:.2f} ms, c = {tp / tq:.2f} -> gamma {g_cal}; "
+        f"both streams busy: {tp_c * 1e3:.2f} / {tq_c * 1e3:.2f} ms, c = {tp_c / tq_c:.2f} -> gamma {g_con}; using {gamma}")
     ctx.rewind(n0)
+
+    if args.phase:
+        phase(args, cfg, ctx, amd, sync, n0, gamma, log)
+        ctx.close()
+        return
 
     if args.sweep:
         sweep(args, cfg, ctx, amd, synth, sync, n0, tp, tq, log)
@@ -354,7 +427,7 @@ def main():
             traffic = json.load(open(tpath)).get(cfg.name, {}).get("gemm_target_bytes_per_launch")
         except Exception:
             traffic = None
-    achieved = bytes_gemm / max(ms_gemm, 1e-9) / 1e6     # bytes/ms -> GB/s
+    in_step = bytes_gemm / max(ms_gemm, 1e-9) / 1e6     # bytes/ms -> GB/s
     out = {
         "metric": "tokens/sec at 1 GPU, 70B/7B-shape pair; verify-pass HBM GB/s % of peak",
         "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": W,
@@ -364,20 +437,29 @@ def main():
                                f"Hq={cfg.target.n_heads} Hkv={cfg.target.n_kv_heads} F={cfg.target.d_ffn}, draft "
                                f"{cfg.draft.n_layers}L d={cfg.draft.d_model}, V={cfg.target.vocab}, batch 1, prompt "
                                f"{cfg.n_prompt}, temperature {cfg.temperature}, gamma {gamma} (c={tp / tq:.2f})",
-                   "gamma": gamma, "c": tp / tq, "n_prompt": cfg.n_prompt, "two_streams": True},
+                   "gamma": gamma, "c": tp / tq, "gamma_both_streams_busy": g_con, "c_both_streams_busy": tp_c / tq_c,
+                   "n_prompt": cfg.n_prompt, "two_streams": True},
         "roofline": {"bound": "hbm", "kernel": "gemm_partial_kernel<1, 8, 0, 4> (target projections)",
-                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": traffic, "launches": int(n_gemm), "avg_launch_us": ms_gemm / max(n_gemm, 1) * 1e3,
-                     "avg_bytes_per_launch": bytes_gemm / max(n_gemm, 1), "read_ceiling_GBps": read_ceiling,
-                     "note": "achieved = weight bytes / HIP-event time of this kernel's launches inside PEARL steps, "
-                             "where it shares HBM with the draft stream: the K timed steps are run a second time "
-                             "(same state, same uniforms, same tokens) with an event pair around every launch, "
-                             "which needs kernel-by-kernel launches and costs instrumented_ms_per_step - ms_per_step; "
-                             "alone_* = same kernel, stream to itself",
+                     "achieved": gemm_alone, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gemm_alone / HBM_PEAK_GBS,
+                     "traffic": traffic, "launches": int(n_a), "avg_launch_us": ms_a / max(n_a, 1) * 1e3,
+                     "avg_bytes_per_launch": bytes_a / max(n_a, 1), "read_ceiling_GBps": read_ceiling,
+                     "note": "achieved = weight bytes of the target's projection launches / their HIP-event durations, "
+                             "measured in this run over 3 verify forwards (M = gamma, context = the prompt) with the GPU "
+                             "to itself: the figure `rocprofv3 --kernel-trace --stats -- python3 bench.py --phase verify` "
+                             "reproduces (profiles/verify_alone_70b_7b_kernel_stats.md; the tracer runs the two streams of "
+                             "a PEARL step one after the other, so only the stream-alone figure can be traced).  "
+                             "in_step_* = the same kernel inside the timed PEARL steps, where it shares the HBM pipe and "
+                             "every CU with the draft stream: the K timed steps run a second time (same state, same "
+                             "uniforms, same tokens) with an event pair around every launch, which needs kernel-by-kernel "
+                             "launches and costs instrumented_ms_per_step - ms_per_step.  traffic is not measured in this "
+                             "run: it is read from profiles/traffic.json (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on the "
+                             "stand-alone projection driver, bytes per launch)",
+                     "in_step_achieved": in_step, "in_step_frac": in_step / HBM_PEAK_GBS,
+                     "in_step_launches": int(n_gemm), "in_step_avg_launch_us": ms_gemm / max(n_gemm, 1) * 1e3,
                      "instrumented_ms_per_step": elapsed_i / max(st_i["steps"], 1) * 1e3,
                      "instrumented_pass_same_tokens": same_tokens,
-                     "alone_achieved": gemm_alone, "alone_frac": gemm_alone / HBM_PEAK_GBS,
-                     "alone_avg_launch_us": ms_a / max(n_a, 1) * 1e3},
+                     "verify_pass_frac_of_peak": alone_stats["verify_mgamma_frac_of_peak"],
+                     "draft_pass_frac_of_peak": alone_stats["draft_frac_of_peak"]},
         "pearl": pearl, "alone": alone_stats, "side": side,
         "prefill": prefill_stats,
         "setup_s": {"build": t_build, "prefill": t_prefill},

@@ -267,16 +267,23 @@ int spec_accept_rows_static(const float* p_logits_dev, int n_rows, const float* 
  * multiples of 32, else SPEC_E_INVAL at spec_prefill); 0 = as a sequence of 32-token verify forwards (the
  * decode kernels); -1 (default) = dense when the shapes allow it and the prompt has more than 64 tokens.
  * Both fill the caches with the same K / V up to bf16 rounding of differently ordered sums.
+ * SPEC_OPT_FUSE_SINGLE: 1 (default) = forwards over a single token (every draft step, autoregressive and pre-verify
+ * target forwards) run seven kernels per layer: the QKV, gate/up and down projections form their input in their
+ * prologue (residual add + norm input, SiLU * mul); 0 = the ten-kernel chain that forwards over several tokens use.
+ * Same operations, sums in the same order up to the grouping of the sums of squares (results agree to fp32
+ * rounding, not bit for bit).
  * SPEC_OPT_TEST_FAIL_PREFILL (tests of the error path only): n > 0 makes the next spec_prefill give up with
  * SPEC_E_NOMEM after its n-th forward, as if the KV pages had run out half way; one-shot.
  * spec_get_option reads a value back; for SPEC_OPT_GEMM_WGS_PER_CU it is the mode the next forward launches with
  * (1 or 2). */
-enum { SPEC_OPT_GEMM_WGS_PER_CU = 1, SPEC_OPT_GRAPHS = 2, SPEC_OPT_PREFILL = 3, SPEC_OPT_TEST_FAIL_PREFILL = 4 };
+enum { SPEC_OPT_GEMM_WGS_PER_CU = 1, SPEC_OPT_GRAPHS = 2, SPEC_OPT_PREFILL = 3, SPEC_OPT_TEST_FAIL_PREFILL = 4,
+       SPEC_OPT_FUSE_SINGLE = 5 };
 int spec_set_option(spec_ctx* ctx, int option, int value);
 int spec_get_option(const spec_ctx* ctx, int option, int* value);
 
-/* Run-time switches: bit 0 = record HIP events around every projection launch of the
- * target forward (read with spec_profile_read). */
+/* Run-time switches: bit 0 = every projection launch of the target forward stamps a pair of HIP events with the
+ * kernel's own start and end times (forwards are then launched kernel by kernel, not as graphs); read with
+ * spec_profile_read. */
 int spec_set_profile(spec_ctx* ctx, int flags);
 /* Sum of the recorded projection-kernel durations (ms) and launch count since the last read. */
 int spec_profile_read(spec_ctx* ctx, double* ms_total, long long* n_launches, double* bytes_total);

@@ -24,6 +24,7 @@ SPEC_OPT_GEMM_WGS_PER_CU = 1
 SPEC_OPT_GRAPHS = 2
 SPEC_OPT_PREFILL = 3
 SPEC_OPT_TEST_FAIL_PREFILL = 4
+SPEC_OPT_FUSE_SINGLE = 5
 EPI_STORE, EPI_RESID, EPI_SWIGLU = 0, 1, 2
 
 

@@ -13,9 +13,14 @@
 // round of 4 panels the 8 wave-partials are summed through LDS in a fixed order and written to
 // P[s][m][n] (fp32).  Consumers add the S slices in ascending order, so results do not depend
 // on timing.
+#include <hip/hip_ext.h>
+
+#include <cstring>
+
 #include "spec_internal.h"
 
 #define GEMM_WAVES 8
+static_assert(GEMM_WAVES == GEMM_WAVES_PER_GROUP, "consumers of the fused projections count 8 S sums of squares");
 #define GEMM_THREADS (GEMM_WAVES * 64)
 #ifndef GEMM_RP
 #define GEMM_RP 4   // panels per reduction round
@@ -92,11 +97,74 @@ __device__ __forceinline__ void mma_chunk(f32x4 (&acc)[MT], const u32x4 (&a)[8],
 // WPE = waves per SIMD the register budget is sized for.  The 16-row variant is held to 128 VGPRs (WPE 4) so
 // that two workgroups share a CU: 16 waves per CU hide the HBM latency far better than 8 (measured 6.9 vs
 // 5.9 TB/s on the gate/up matrix), and the second slot can also go to the other stream's kernel.
-template <int MT, int SPWMAX, int TAG, int WPE>
+// ---- prologues of the single-token projections (PRO != PRO_NONE, M = 1) ------------------------------------
+// A wave forms the activation values of its own K range (at most 256 columns): lane l the four columns
+// k0 + 4 l .. + 3, all loads of a lane independent of each other.  The bf16 results go through LDS into operand
+// order.  Every sum runs in the order the stand-alone kernels use (K slices ascending), so the values are the ones
+// the three-kernel chain would produce.
+__device__ __forceinline__ unsigned pack_bf16x2(float a, float b) {
+  const bf16 x = __float2bfloat16(a), y = __float2bfloat16(b);
+  return (unsigned)__builtin_bit_cast(unsigned short, x) | ((unsigned)__builtin_bit_cast(unsigned short, y) << 16);
+}
+
+// h_in + sum of the K slices (ascending), four independent loads in flight
+__device__ __forceinline__ f32x4 sum_slices(f32x4 t, const f32x4* __restrict__ P4, size_t sstride4, int S) {
+  int s = 0;
+  for (; s + 4 <= S; s += 4) {
+    const f32x4 p0 = P4[(size_t)(s + 0) * sstride4], p1 = P4[(size_t)(s + 1) * sstride4];
+    const f32x4 p2 = P4[(size_t)(s + 2) * sstride4], p3 = P4[(size_t)(s + 3) * sstride4];
+    t += p0; t += p1; t += p2; t += p3;
+  }
+  for (; s < S; ++s) t += P4[(size_t)s * sstride4];
+  return t;
+}
+
+template <int PRO>
+__device__ __forceinline__ void prologue_values(const GemmPro& pro, int K, int k, bool valid, bool first_group, int ws,
+                                                int lane, uint2* __restrict__ dst) {
+  f32x4 r = {0.f, 0.f, 0.f, 0.f};
+  if (PRO == PRO_ADDNORM) {
+    // residual add, sums of squares, x' = bf16(h * gain) (the consumers of this projection apply 1 / rms)
+    f32x4 t = {0.f, 0.f, 0.f, 0.f};
+    if (valid) {
+      t = *reinterpret_cast<const f32x4*>(pro.h_in + k);
+      if (pro.part) t = sum_slices(t, reinterpret_cast<const f32x4*>(pro.part) + (k >> 2), (size_t)(K >> 2), pro.S);
+      const bf16* g = pro.gain + k;
+      r = f32x4{t.x * __bfloat162float(g[0]), t.y * __bfloat162float(g[1]), t.z * __bfloat162float(g[2]),
+                t.w * __bfloat162float(g[3])};
+    }
+    if (first_group) {
+      if (valid) *reinterpret_cast<f32x4*>(pro.h_out + k) = t;
+      float ss = t.x * t.x + t.y * t.y + t.z * t.z + t.w * t.w;
+#pragma unroll
+      for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
+      if (lane == 0) pro.ssq_out[ws] = ss;
+    }
+  } else if (PRO == PRO_SWIGLU) {
+    if (valid) {
+      const int gc = (k >> 4) * 32 + (k & 15);          // gate panel of 16 columns, then the up panel
+      const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+      const f32x4* P4 = reinterpret_cast<const f32x4*>(pro.part + gc);
+      const f32x4 g = sum_slices(zero, P4, (size_t)(K >> 1), pro.S);
+      const f32x4 u = sum_slices(zero, P4 + 4, (size_t)(K >> 1), pro.S);
+      const float inv = pro.rs.inv(0);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float gv = g[i] * inv, uv = u[i] * inv;
+        r[i] = gv / (1.0f + __expf(-gv)) * uv;
+      }
+    }
+  }
+  dst[0] = make_uint2(pack_bf16x2(r.x, r.y), pack_bf16x2(r.z, r.w));
+}
+
+template <int MT, int SPWMAX, int TAG, int WPE, int PRO>
 __global__ __launch_bounds__(GEMM_THREADS, WPE) void gemm_partial_kernel(const bf16* __restrict__ X,
                                                                     const u32x4* __restrict__ Wp,
                                                                     float* __restrict__ P, int M, int N, int K,
-                                                                    int NT, int steps, int S, int spw, int Gs) {
+                                                                    int NT, int steps, int S, int spw, int Gs,
+                                                                    GemmPro pro) {
+  static_assert(PRO == PRO_NONE || MT == 1, "the fused prologues exist for single-token forwards only");
   constexpr int NCH = SPWMAX / 8;            // chunks per panel
   constexpr int UNITS = GEMM_RP * NCH;       // chunks per reduction round (even)
   constexpr int NBUF = (MT == 1) ? 2 : 1;    // LDS reduction buffers: two let a round end with a single barrier
@@ -112,28 +180,47 @@ __global__ __launch_bounds__(GEMM_THREADS, WPE) void gemm_partial_kernel(const b
   const int step0 = (int)((long long)ws * steps / nws);
   const int nst = (int)((long long)(ws + 1) * steps / nws) - step0;   // <= spw <= SPWMAX
 
-  // activation fragments of this wave's K range, kept for the whole kernel
-  bf16x8 b[MT][SPWMAX];
-#pragma unroll
-  for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-    for (int j = 0; j < SPWMAX; ++j) {
-      const int m = mt * 16 + c;
-      const int k = (step0 + j) * 32 + kb * 8;
-      u32x4 v = {0u, 0u, 0u, 0u};
-      if (j < nst && m < M && k < K) v = *reinterpret_cast<const u32x4*>(X + (size_t)m * K + k);
-      b[mt][j] = __builtin_bit_cast(bf16x8, v);
-    }
-
   const u32x4* wbase = Wp + (size_t)step0 * 64 + lane;
   const size_t pstride = (size_t)steps * 64;   // 16-byte units per panel
   // Two-deep software pipeline over the chunk sequence (panel-major, NCH chunks per panel): chunks q and
   // q+1 are in flight; once chunk q is consumed its buffer is refilled with chunk q+2.  The sequence runs on
-  // across reduction rounds, so the loads never drain at a round's barrier.
+  // across reduction rounds, so the loads never drain at a round's barrier.  The first two chunks are requested
+  // before anything else: whatever the activations cost (a plain load, or a fused prologue with dependent loads
+  // of its own) then runs under the start of the weight stream.
   u32x4 a[2][8];
 #pragma unroll
   for (int q = 0; q < 2; ++q)
     if (p0 + q / NCH < p1) load_chunk(a[q], wbase + (size_t)(p0 + q / NCH) * pstride, (q % NCH) * 8, nst);
+
+  // activation fragments of this wave's K range, kept for the whole kernel
+  bf16x8 b[MT][SPWMAX];
+  if (PRO == PRO_NONE) {
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int j = 0; j < SPWMAX; ++j) {
+        const int m = mt * 16 + c;
+        const int k = (step0 + j) * 32 + kb * 8;
+        u32x4 v = {0u, 0u, 0u, 0u};
+        if (j < nst && m < M && k < K) v = *reinterpret_cast<const u32x4*>(X + (size_t)m * K + k);
+        b[mt][j] = __builtin_bit_cast(bf16x8, v);
+      }
+  } else {
+    // the wave's (at most) 256 columns: formed four per lane, handed over in operand order through LDS (the
+    // reduction buffer is not in use yet)
+    unsigned short* stage = reinterpret_cast<unsigned short*>(&red[0][0][0][0][0]) + w * (SPWMAX * 32);
+    const int kk = step0 * 32 + 4 * lane;
+    const bool valid = 4 * lane < nst * 32 && kk < K;
+    prologue_values<PRO>(pro, K, kk, valid, idx == 0, ws, lane, reinterpret_cast<uint2*>(stage) + lane);
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < SPWMAX; ++j) {
+      u32x4 v = {0u, 0u, 0u, 0u};
+      if (j < nst && c == 0) v = *reinterpret_cast<const u32x4*>(stage + j * 32 + kb * 8);
+      b[0][j] = __builtin_bit_cast(bf16x8, v);
+    }
+    __syncthreads();   // the staging area is the reduction buffer of the first round
+  }
 
   int rb = 0;
   for (int pr = p0; pr < p1; pr += GEMM_RP) {
@@ -175,22 +262,42 @@ __global__ __launch_bounds__(GEMM_THREADS, WPE) void gemm_partial_kernel(const b
   }
 }
 
-template <int TAG>
-static void launch_tagged(const GemmPlan& p, const bf16* x, const void* wp, float* partials, hipStream_t st) {
+// ev0 / ev1 (both or neither): events that receive the kernel's own start and end time stamps (the ones a
+// kernel trace shows), not the time of event packets around it
+template <int TAG, int PRO>
+static void launch_tagged(const GemmPlan& p, const bf16* x, const void* wp, float* partials, hipStream_t st,
+                          hipEvent_t ev0, hipEvent_t ev1, const GemmPro& pro) {
   dim3 grid(p.Gs * p.S), block(GEMM_THREADS);
   if (p.MT == 1)
-    gemm_partial_kernel<1, 8, TAG, 4><<<grid, block, 0, st>>>(x, (const u32x4*)wp, partials, p.M, p.N, p.K, p.NT,
-                                                               p.steps, p.S, p.spw, p.Gs);
-  else
-    gemm_partial_kernel<2, 8, TAG, 2><<<grid, block, 0, st>>>(x, (const u32x4*)wp, partials, p.M, p.N, p.K, p.NT,
-                                                               p.steps, p.S, p.spw, p.Gs);
+    hipExtLaunchKernelGGL((gemm_partial_kernel<1, 8, TAG, 4, PRO>), grid, block, 0, st, ev0, ev1, 0, x,
+                          (const u32x4*)wp, partials, p.M, p.N, p.K, p.NT, p.steps, p.S, p.spw, p.Gs, pro);
+  else if (PRO == PRO_NONE)
+    hipExtLaunchKernelGGL((gemm_partial_kernel<2, 8, TAG, 2, PRO_NONE>), grid, block, 0, st, ev0, ev1, 0, x,
+                          (const u32x4*)wp, partials, p.M, p.N, p.K, p.NT, p.steps, p.S, p.spw, p.Gs, pro);
 }
 
 hipError_t launch_gemm_partials(const GemmPlan& p, const bf16* x, const void* wp, float* partials, hipStream_t st,
-                                int tag) {
-  if (tag == 0) launch_tagged<0>(p, x, wp, partials, st);
-  else if (tag == 1) launch_tagged<1>(p, x, wp, partials, st);
-  else launch_tagged<2>(p, x, wp, partials, st);
+                                int tag, hipEvent_t ev0, hipEvent_t ev1) {
+  GemmPro none;
+  memset(&none, 0, sizeof(none));
+  if (tag == 0) launch_tagged<0, PRO_NONE>(p, x, wp, partials, st, ev0, ev1, none);
+  else if (tag == 1) launch_tagged<1, PRO_NONE>(p, x, wp, partials, st, ev0, ev1, none);
+  else launch_tagged<2, PRO_NONE>(p, x, wp, partials, st, ev0, ev1, none);
+  return hipGetLastError();
+}
+
+template <int TAG>
+static void launch_fused_tagged(const GemmPlan& p, const GemmPro& pro, const void* wp, float* partials, hipStream_t st,
+                                hipEvent_t ev0, hipEvent_t ev1) {
+  if (pro.kind == PRO_ADDNORM) launch_tagged<TAG, PRO_ADDNORM>(p, nullptr, wp, partials, st, ev0, ev1, pro);
+  else launch_tagged<TAG, PRO_SWIGLU>(p, nullptr, wp, partials, st, ev0, ev1, pro);
+}
+
+hipError_t launch_gemm_fused(const GemmPlan& p, const GemmPro& pro, const void* wp, float* partials, hipStream_t st,
+                             int tag, hipEvent_t ev0, hipEvent_t ev1) {
+  if (p.M != 1 || p.MT != 1 || pro.kind < PRO_ADDNORM || pro.kind > PRO_SWIGLU || (p.K & 3)) return hipErrorInvalidValue;
+  if (tag == 0) launch_fused_tagged<0>(p, pro, wp, partials, st, ev0, ev1);
+  else launch_fused_tagged<1>(p, pro, wp, partials, st, ev0, ev1);
   return hipGetLastError();
 }
 

@@ -163,7 +163,7 @@ __global__ __launch_bounds__(ADDSQ_THREADS) void add_sumsq_kernel(float* __restr
     float tot = 0.f;
 #pragma unroll
     for (int k = 0; k < ADDSQ_THREADS / 64; ++k) tot += sh[k];
-    ssq[m * ADDSQ_MAX_PIECES + w] = tot;
+    ssq[m * SSQ_STRIDE + w] = tot;
   }
 }
 hipError_t launch_add_sumsq(float* h, const float* partials, int S, const bf16* gain, bf16* a, float* ssq, int M,

@@ -38,34 +38,72 @@ struct GemmPlan {
 // wgs_per_cu: 2 = fill both workgroup slots of every CU (a stream running alone), 1 = leave one slot to
 // the other stream's kernels.  The K split (S, spw) does not depend on it.
 GemmPlan gemm_plan(int M, int N, int K, int wgs_per_cu = 2);
+// ev0 / ev1: optional events that receive the kernel's own start / end time stamps
 hipError_t launch_gemm_partials(const GemmPlan& p, const bf16* x, const void* wp, float* partials, hipStream_t st,
-                                int tag);
+                                int tag, hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr);
+
 // The RMSNorm of the decode path is split in three: the residual-add kernel stores x' = bf16(h * gain) and the
 // rows' sums of squares (W pieces per row); the projection runs on x' unchanged; whoever adds the projection's K
 // slices multiplies the sum by inv_m = 1 / sqrt(sum_w ssq[m][w] / d + eps) (the projection is linear in its rows
 // and bf16 keeps the same relative precision at any scale).  ssq == nullptr: no scaling.
+#define SSQ_STRIDE 128                     // floats per row of sums of squares
+static_assert(SSQ_STRIDE % 4 == 0, "RowScale::inv reads the pieces as 16-byte vectors");
 struct RowScale {
-  const float* ssq;    // [rows][ADDSQ_MAX_PIECES], pieces beyond W are zero
+  const float* ssq;    // [rows][SSQ_STRIDE], W pieces in use (whatever lies behind them is ignored)
   int W, d;
   float eps;
 #ifdef __HIPCC__
-  // the row's pieces come in up to four independent 16-byte loads (one round trip) and are added in ascending order
+  // the row's pieces come in independent 16-byte loads, four in flight (one round trip for up to 16 pieces), and
+  // are added in ascending order
   __device__ __forceinline__ float inv(int m) const {
     if (!ssq) return 1.0f;
-    const f32x4* p = reinterpret_cast<const f32x4*>(ssq + (size_t)m * 16);
+    const f32x4* p = reinterpret_cast<const f32x4*>(ssq + (size_t)m * SSQ_STRIDE);
     const int nv = (W + 3) >> 2;
-    f32x4 v[4];
-#pragma unroll
-    for (int k = 0; k < 4; ++k) v[k] = (k < nv) ? p[k] : f32x4{0.f, 0.f, 0.f, 0.f};
     float tot = 0.f;
+    for (int k0 = 0; k0 < nv; k0 += 4) {
+      f32x4 v[4];
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      tot += v[k].x; tot += v[k].y; tot += v[k].z; tot += v[k].w;
+      for (int k = 0; k < 4; ++k) v[k] = (k0 + k < nv) ? p[k0 + k] : f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const int i0 = (k0 + k) * 4;
+        tot += (i0 + 0 < W) ? v[k].x : 0.f; tot += (i0 + 1 < W) ? v[k].y : 0.f;
+        tot += (i0 + 2 < W) ? v[k].z : 0.f; tot += (i0 + 3 < W) ? v[k].w : 0.f;
+      }
     }
     return 1.0f / sqrtf(tot / (float)d + eps);
   }
 #endif
 };
+
+// ---------------------------------------------------------------------------------------
+// Single-token forwards (M = 1: every draft step, autoregressive and pre-verify target forwards) fold the residual
+// add + RMSNorm input and the SiLU * mul into the prologue of the projection that consumes them: a wave forms the
+// activation fragments of its own K range itself, after its first weight loads are on their way, so the dependent
+// loads hide behind the start of the weight stream and three kernel boundaries per layer disappear.
+// ---------------------------------------------------------------------------------------
+enum { PRO_NONE = 0, PRO_ADDNORM = 1, PRO_SWIGLU = 2 };
+#define GEMM_WAVES_PER_GROUP 8   // waves of a projection workgroup: a PRO_ADDNORM launch leaves 8 S sums of squares
+struct GemmPro {
+  int kind;
+  // PRO_ADDNORM: x' = bf16((h_in + sum_s part[s]) * gain); the workgroups of the first panel range also store the new
+  // residual stream to h_out (another buffer than h_in: the other workgroups still read h_in) and one sum of
+  // squares per wave to ssq[0 .. 8 S)
+  const float* h_in;
+  float* h_out;
+  const bf16* gain;
+  float* ssq_out;
+  // PRO_ADDNORM, PRO_SWIGLU: K-slice partial sums of the producing projection, [S][width]
+  const float* part;
+  int S;
+  // PRO_SWIGLU: z = bf16(silu(g * inv) * (u * inv)), gate / up panels interleaved in `part` (width 2 K)
+  RowScale rs;
+};
+// the same projection for M = 1 with the activation formed in the prologue (pro.kind != PRO_NONE)
+hipError_t launch_gemm_fused(const GemmPlan& p, const GemmPro& pro, const void* wp, float* partials, hipStream_t st,
+                             int tag, hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr);
+
+
 // n = M * N elements; rs scales row i / N (N given) of the sum
 hipError_t launch_reduce_partials(float* y, const float* partials, int S, size_t n, hipStream_t st,
                                   RowScale rs = RowScale{nullptr, 0, 0, 0.f}, int N = 0);
@@ -105,10 +143,10 @@ hipError_t launch_embed(float* h, const bf16* embed, const int* tok, int M, int 
 hipError_t launch_addnorm(float* h, const float* partials, int S, const bf16* gain, bf16* a, int M, int d,
                           float eps, hipStream_t st);
 // h += sum_s partials[s] (if partials), a = bf16(h * gain) (not normalised), ssq[m][w] = sum of h^2 over the w-th
-// piece of 1024 columns of row m (row stride ADDSQ_MAX_PIECES; the caller zeroes the buffer once, pieces beyond W
+// piece of 1024 columns of row m (row stride SSQ_STRIDE; pieces beyond W
 // are never written); returns the number of pieces W through *W_out
 #define ADDSQ_MAX_PIECES 16
-static_assert(ADDSQ_MAX_PIECES == 16, "RowScale::inv reads a row of sums of squares as four 16-byte vectors");
+static_assert(ADDSQ_MAX_PIECES <= SSQ_STRIDE, "a row of sums of squares holds every piece");
 hipError_t launch_add_sumsq(float* h, const float* partials, int S, const bf16* gain, bf16* a, float* ssq, int M,
                             int d, int* W_out, hipStream_t st);
 // tab: optional [M][dh/2] (cos, sin) table from launch_rope_table for the same len; nullptr = compute in place

@@ -11,6 +11,24 @@ from . import ALGO_AR, ALGO_PEARL, ALGO_SD, SPEC_DRAFT, SPEC_TARGET
 from .binding import PackedModel, SpecContext, pack_from_dict, pack_model
 
 
+def _library_generated_model(shape: synth.ModelShape, seed: int, device: str) -> PackedModel:
+    """Same shapes and distributions from PyTorch's own generator (other values): for runs under the profiler's
+    counter collection, which crashes on the run-time-compiled kernel behind the counter-based generator's inverse
+    normal CDF.  Never used where values are compared with the oracle."""
+    mats = synth.layer_matrix_shapes(shape)
+    gen = torch.Generator(device=device)
+    gen.manual_seed(seed)
+
+    def get(layer: Optional[int], name: str) -> torch.Tensor:
+        if name in ("final_norm", "attn_norm", "ffn_norm"):
+            g = torch.empty(shape.d_model, dtype=torch.float32, device=device).normal_(0.0, synth.GAIN_STD, generator=gen)
+            return (1.0 + g).to(torch.bfloat16)
+        shp = (shape.vocab, shape.d_model) if layer is None else mats[name]
+        return torch.empty(shp, dtype=torch.float32, device=device).normal_(0.0, 0.02, generator=gen).to(torch.bfloat16)
+
+    return pack_model(shape, get, device)
+
+
 def _generated_model(shape: synth.ModelShape, seed: int, device: str) -> PackedModel:
     """Generate each tensor on the device with the counter-based generator, pack it, drop the source."""
     mats = synth.layer_matrix_shapes(shape)
@@ -28,9 +46,11 @@ def _generated_model(shape: synth.ModelShape, seed: int, device: str) -> PackedM
     return pack_model(shape, get, device)
 
 
-def build_pair(cfg: synth.PairConfig, device: str = "cuda", weights: Optional[Tuple[dict, dict]] = None):
+def build_pair(cfg: synth.PairConfig, device: str = "cuda", weights: Optional[Tuple[dict, dict]] = None,
+               library_generator: bool = False):
     """(target PackedModel, draft PackedModel) for a workload.  With `weights` (generator dicts, e.g. the
-    ones also handed to a reference implementation) those exact values are packed instead."""
+    ones also handed to a reference implementation) those exact values are packed instead.  library_generator:
+    values from PyTorch's generator instead of the counter-based one (profiler counter runs only)."""
     if weights is not None:
         tw, dw = weights
         target = pack_from_dict(cfg.target, tw, device)
@@ -39,11 +59,12 @@ def build_pair(cfg: synth.PairConfig, device: str = "cuda", weights: Optional[Tu
         else:
             draft = pack_from_dict(cfg.draft, dw, device)
         return target, draft
-    target = _generated_model(cfg.target, cfg.seed_target, device)
+    make = _library_generated_model if library_generator else _generated_model
+    target = make(cfg.target, cfg.seed_target, device)
     if cfg.draft_from_target_layers:
         draft = target.prefix(cfg.draft_from_target_layers, cfg.draft)
     else:
-        draft = _generated_model(cfg.draft, cfg.seed_draft, device)
+        draft = make(cfg.draft, cfg.seed_draft, device)
     return target, draft
 
 

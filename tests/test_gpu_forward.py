@@ -88,6 +88,35 @@ def test_multi_token_verify_equals_sequential_single_token_forwards_on_gpu():
     ctx.close()
 
 
+@pytest.mark.parametrize("case", list(CASES))
+def test_single_token_forwards_with_fused_prologues_equal_the_general_chain(case):
+    """Forwards over one token run seven kernels per layer (projections that form their own input) instead of ten.
+    Same operations and the same order of every K-slice sum; only the sums of squares are grouped by wave instead of
+    by 1024 columns.  Both chains against the oracle, and against each other far below the bf16 tolerance; the
+    caches they leave are interchangeable (a multi-token forward behind either gives the same logits)."""
+    cfg = CASES[case]()
+    amd, ctx, tm, dm = _setup(cfg)
+    prompt = synth.prompt_tokens(97, cfg.target.vocab, 7).tolist()
+    toks = synth.prompt_tokens(12, cfg.target.vocab, 8).tolist()
+    ocm = transformer.CachedModel(tm, 256)
+    ocm.feed(prompt[:-1])
+    ref = np.concatenate([ocm.feed([t]) for t in [prompt[-1]] + toks[:5]])
+    ref_multi = ocm.feed(toks[5:])
+    outs = {}
+    for fused in (1, 0):
+        ctx.set_option(amd.SPEC_OPT_FUSE_SINGLE, fused)
+        assert ctx.get_option(amd.SPEC_OPT_FUSE_SINGLE) == fused
+        ctx.prefill(prompt)
+        single = np.concatenate([ctx.verify([t], want_logits=True) for t in [prompt[-1]] + toks[:5]])
+        multi = ctx.verify(toks[5:], want_logits=True)
+        assert _rel_err(single, ref) <= LOGIT_TOL and _rel_err(multi, ref_multi) <= LOGIT_TOL
+        outs[fused] = (single, multi)
+    e1, e2 = _rel_err(outs[1][0], outs[0][0]), _rel_err(outs[1][1], outs[0][1])
+    print(f"  {case}: fused vs general single-token chain {e1:.2e}, multi-token forward behind them {e2:.2e}", flush=True)
+    assert e1 < 2e-3 and e2 < 2e-3
+    ctx.close()
+
+
 def test_rollback_is_bit_exact_and_returns_pages():
     cfg = CASES["gqa64"]()
     amd, ctx, tm, dm = _setup(cfg, extra_seq=256)
