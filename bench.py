@@ -47,6 +47,7 @@ def parse():
                     help="weights of the same shapes and distributions from PyTorch's generator instead of the counter-based "
                          "one: for runs under rocprofv3 --pmc, whose counter collection crashes on PyTorch's run-time-compiled "
                          "inverse-normal kernel (kernel counters do not depend on the values)")
+    ap.add_argument("--rows", type=int, default=0, help="with --phase verify / verify-graph: tokens per forward (default gamma)")
     ap.add_argument("--fuse", type=int, default=-1, help="SPEC_OPT_FUSE_SINGLE value (experiments)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
     ap.add_argument("--no-side", action="store_true", help="skip AR / SD / forced-acceptance side runs")
@@ -227,7 +228,7 @@ def phase(args, cfg, ctx, amd, sync, n0, gamma, log):
             ctx.rewind(n0)
             done += k
 
-    for m in ((1, gamma) if verify else (1,)):
+    for m in ((args.rows or gamma,) if verify else (1,)):
         b = forward_bytes(shape, n0 - 1, m)
         if args.phase == "verify":
             ctx.set_profile(1); ctx.profile_read()

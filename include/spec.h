@@ -281,11 +281,12 @@ enum { SPEC_OPT_GEMM_WGS_PER_CU = 1, SPEC_OPT_GRAPHS = 2, SPEC_OPT_PREFILL = 3, 
 int spec_set_option(spec_ctx* ctx, int option, int value);
 int spec_get_option(const spec_ctx* ctx, int option, int* value);
 
-/* Run-time switches: bit 0 = every projection launch of the target forward stamps a pair of HIP events with the
- * kernel's own start and end times (forwards are then launched kernel by kernel, not as graphs); read with
- * spec_profile_read. */
+/* Run-time switches: bit 0 = every projection launch of the target forward records its own duration: its
+ * workgroups stamp the device's constant-rate wall clock on the way in and out, the earliest start and the latest end
+ * are kept per launch (no dispatch overhead in it, unlike events around a launch; up to 65536 launches between two
+ * reads).  Forwards are then launched kernel by kernel, not as graphs.  Read with spec_profile_read. */
 int spec_set_profile(spec_ctx* ctx, int flags);
-/* Sum of the recorded projection-kernel durations (ms) and launch count since the last read. */
+/* Sum of the recorded projection-kernel durations (ms), launch count and weight bytes since the last read. */
 int spec_profile_read(spec_ctx* ctx, double* ms_total, long long* n_launches, double* bytes_total);
 
 #ifdef __cplusplus

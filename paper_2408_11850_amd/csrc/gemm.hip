@@ -13,8 +13,6 @@
 // round of 4 panels the 8 wave-partials are summed through LDS in a fixed order and written to
 // P[s][m][n] (fp32).  Consumers add the S slices in ascending order, so results do not depend
 // on timing.
-#include <hip/hip_ext.h>
-
 #include <cstring>
 
 #include "spec_internal.h"
@@ -175,6 +173,8 @@ __global__ __launch_bounds__(GEMM_THREADS, WPE) void gemm_partial_kernel(const b
   const int p1 = (int)((long long)(idx + 1) * NT / Gs);
   const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int c = lane & 15, kb = lane >> 4;
+  if (pro.stamp && threadIdx.x == 0)
+    atomicMax(pro.stamp + 2 * (blockIdx.x % STAMP_WAYS), ~(unsigned long long)wall_clock64());
   // the K steps are dealt evenly to the S * 8 waves that share a panel: floor / ceil of steps / (8 S) each
   const int ws = s * GEMM_WAVES + w, nws = S * GEMM_WAVES;
   const int step0 = (int)((long long)ws * steps / nws);
@@ -260,44 +260,44 @@ __global__ __launch_bounds__(GEMM_THREADS, WPE) void gemm_partial_kernel(const b
     if (NBUF == 2) rb ^= 1;
     else __syncthreads();
   }
+  if (pro.stamp && threadIdx.x == 0)
+    atomicMax(pro.stamp + 2 * (blockIdx.x % STAMP_WAYS) + 1, (unsigned long long)wall_clock64());
 }
 
-// ev0 / ev1 (both or neither): events that receive the kernel's own start and end time stamps (the ones a
-// kernel trace shows), not the time of event packets around it
 template <int TAG, int PRO>
 static void launch_tagged(const GemmPlan& p, const bf16* x, const void* wp, float* partials, hipStream_t st,
-                          hipEvent_t ev0, hipEvent_t ev1, const GemmPro& pro) {
+                          const GemmPro& pro) {
   dim3 grid(p.Gs * p.S), block(GEMM_THREADS);
   if (p.MT == 1)
-    hipExtLaunchKernelGGL((gemm_partial_kernel<1, 8, TAG, 4, PRO>), grid, block, 0, st, ev0, ev1, 0, x,
-                          (const u32x4*)wp, partials, p.M, p.N, p.K, p.NT, p.steps, p.S, p.spw, p.Gs, pro);
+    gemm_partial_kernel<1, 8, TAG, 4, PRO><<<grid, block, 0, st>>>(x, (const u32x4*)wp, partials, p.M, p.N, p.K, p.NT,
+                                                                     p.steps, p.S, p.spw, p.Gs, pro);
   else if (PRO == PRO_NONE)
-    hipExtLaunchKernelGGL((gemm_partial_kernel<2, 8, TAG, 2, PRO_NONE>), grid, block, 0, st, ev0, ev1, 0, x,
-                          (const u32x4*)wp, partials, p.M, p.N, p.K, p.NT, p.steps, p.S, p.spw, p.Gs, pro);
+    gemm_partial_kernel<2, 8, TAG, 2, PRO_NONE><<<grid, block, 0, st>>>(x, (const u32x4*)wp, partials, p.M, p.N, p.K,
+                                                                          p.NT, p.steps, p.S, p.spw, p.Gs, pro);
 }
 
 hipError_t launch_gemm_partials(const GemmPlan& p, const bf16* x, const void* wp, float* partials, hipStream_t st,
-                                int tag, hipEvent_t ev0, hipEvent_t ev1) {
+                                int tag, unsigned long long* stamp) {
   GemmPro none;
   memset(&none, 0, sizeof(none));
-  if (tag == 0) launch_tagged<0, PRO_NONE>(p, x, wp, partials, st, ev0, ev1, none);
-  else if (tag == 1) launch_tagged<1, PRO_NONE>(p, x, wp, partials, st, ev0, ev1, none);
-  else launch_tagged<2, PRO_NONE>(p, x, wp, partials, st, ev0, ev1, none);
+  none.stamp = stamp;
+  if (tag == 0) launch_tagged<0, PRO_NONE>(p, x, wp, partials, st, none);
+  else if (tag == 1) launch_tagged<1, PRO_NONE>(p, x, wp, partials, st, none);
+  else launch_tagged<2, PRO_NONE>(p, x, wp, partials, st, none);
   return hipGetLastError();
 }
 
 template <int TAG>
-static void launch_fused_tagged(const GemmPlan& p, const GemmPro& pro, const void* wp, float* partials, hipStream_t st,
-                                hipEvent_t ev0, hipEvent_t ev1) {
-  if (pro.kind == PRO_ADDNORM) launch_tagged<TAG, PRO_ADDNORM>(p, nullptr, wp, partials, st, ev0, ev1, pro);
-  else launch_tagged<TAG, PRO_SWIGLU>(p, nullptr, wp, partials, st, ev0, ev1, pro);
+static void launch_fused_tagged(const GemmPlan& p, const GemmPro& pro, const void* wp, float* partials, hipStream_t st) {
+  if (pro.kind == PRO_ADDNORM) launch_tagged<TAG, PRO_ADDNORM>(p, nullptr, wp, partials, st, pro);
+  else launch_tagged<TAG, PRO_SWIGLU>(p, nullptr, wp, partials, st, pro);
 }
 
 hipError_t launch_gemm_fused(const GemmPlan& p, const GemmPro& pro, const void* wp, float* partials, hipStream_t st,
-                             int tag, hipEvent_t ev0, hipEvent_t ev1) {
+                             int tag) {
   if (p.M != 1 || p.MT != 1 || pro.kind < PRO_ADDNORM || pro.kind > PRO_SWIGLU || (p.K & 3)) return hipErrorInvalidValue;
-  if (tag == 0) launch_fused_tagged<0>(p, pro, wp, partials, st, ev0, ev1);
-  else launch_fused_tagged<1>(p, pro, wp, partials, st, ev0, ev1);
+  if (tag == 0) launch_fused_tagged<0>(p, pro, wp, partials, st);
+  else launch_fused_tagged<1>(p, pro, wp, partials, st);
   return hipGetLastError();
 }
 

@@ -68,10 +68,11 @@ struct ModelRt {
   float2* pf_rope = nullptr;      // (cos, sin) per token and rotation pair of the current block
 };
 
-struct ProfEvents {
-  std::vector<hipEvent_t> ev;     // pairs
-  size_t used = 0;
+struct ProfStamps {               // per profiled projection launch: the kernel's own (start, end) stamps
+  unsigned long long* dev = nullptr;   // [cap][STAMP_WAYS][2], zeroed; see GemmPro::stamp
+  size_t cap = 0, used = 0;
   double bytes = 0.0;
+  double tick_s = 0.0;            // seconds per tick of the device's wall clock
 };
 
 }  // namespace
@@ -101,7 +102,7 @@ struct spec_ctx {
   bool fuse_single = true;        // single-token forwards through the projections with fused prologues
   int prefill_opt = -1;           // -1 automatic, 0 = 32-token verify forwards, 1 = dense path
   int fail_prefill_after = 0;     // test hook: > 0 = the next spec_prefill gives up after that many forwards
-  ProfEvents prof;
+  ProfStamps prof;
 };
 
 namespace {
@@ -229,19 +230,25 @@ int ensure_pages(ModelRt& m, int new_len) {
   return SPEC_OK;
 }
 
-// the next pair of profiling events (created on demand)
-int prof_events(spec_ctx* c, double bytes, hipEvent_t* e0, hipEvent_t* e1) {
-  ProfEvents& p = c->prof;
-  if (p.used + 2 > p.ev.size()) {
-    for (int i = 0; i < 2; ++i) {
-      hipEvent_t e;
-      HIPCHK(hipEventCreate(&e));
-      p.ev.push_back(e);
-    }
+#define PROF_MAX_LAUNCHES 65536
+// the stamp words of the next profiled projection launch (nullptr once the buffer is full: later launches run untimed)
+int prof_slot(spec_ctx* c, double bytes, unsigned long long** slot) {
+  ProfStamps& p = c->prof;
+  *slot = nullptr;
+  if (!p.dev) {
+    int rc = dev_alloc(&p.dev, (size_t)PROF_MAX_LAUNCHES * 2 * STAMP_WAYS);
+    if (rc) return rc;
+    HIPCHK(hipMemset(p.dev, 0, (size_t)PROF_MAX_LAUNCHES * 2 * STAMP_WAYS * sizeof(unsigned long long)));
+    int dev = 0, khz = 0;
+    HIPCHK(hipGetDevice(&dev));
+    HIPCHK(hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev));
+    if (khz < 1) FAIL(SPEC_E_HIP, "device reports a wall clock rate of %d kHz", khz);
+    p.tick_s = 1.0 / (1e3 * khz);
+    p.cap = PROF_MAX_LAUNCHES;
   }
-  *e0 = p.ev[p.used];
-  *e1 = p.ev[p.used + 1];
-  p.used += 2;
+  if (p.used >= p.cap) return SPEC_OK;
+  *slot = p.dev + (size_t)2 * STAMP_WAYS * p.used;
+  p.used++;
   p.bytes += bytes;
   return SPEC_OK;
 }
@@ -249,11 +256,10 @@ int prof_events(spec_ctx* c, double bytes, hipEvent_t* e0, hipEvent_t* e1) {
 int run_gemm(spec_ctx* c, int which, ModelRt& m, int M, int N, int K, const bf16* x, const void* w, GemmPlan* plan_out) {
   GemmPlan p = gemm_plan(M, N, K, c->wgs);
   const bool prof = (c->profile_flags & 1) && which == SPEC_TARGET;
-  hipEvent_t e0 = nullptr, e1 = nullptr;
+  unsigned long long* slot = nullptr;
   int rc;
-  // profiling: the launch itself stamps the two events with the kernel's start and end
-  if (prof && (rc = prof_events(c, (double)p.weight_bytes(), &e0, &e1))) return rc;
-  HIPCHK(launch_gemm_partials(p, x, w, m.partials, m.stream, which, e0, e1));
+  if (prof && (rc = prof_slot(c, (double)p.weight_bytes(), &slot))) return rc;
+  HIPCHK(launch_gemm_partials(p, x, w, m.partials, m.stream, which, slot));
   *plan_out = p;
   return SPEC_OK;
 }
@@ -310,19 +316,18 @@ int enqueue_forward(spec_ctx* c, int which, int M, int logit_rows, int l0, int l
 // a plain projection into a given buffer of K-slice sums
 int run_gemm_into(spec_ctx* c, int which, ModelRt& m, const GemmPlan& p, const bf16* x, const void* w, float* out) {
   const bool prof = (c->profile_flags & 1) && which == SPEC_TARGET;
-  hipEvent_t e0 = nullptr, e1 = nullptr;
+  unsigned long long* slot = nullptr;
   int rc;
-  if (prof && (rc = prof_events(c, (double)p.weight_bytes(), &e0, &e1))) return rc;
-  HIPCHK(launch_gemm_partials(p, x, w, out, m.stream, which, e0, e1));
+  if (prof && (rc = prof_slot(c, (double)p.weight_bytes(), &slot))) return rc;
+  HIPCHK(launch_gemm_partials(p, x, w, out, m.stream, which, slot));
   return SPEC_OK;
 }
 
-int run_gemm_fused(spec_ctx* c, int which, ModelRt& m, const GemmPlan& p, const GemmPro& pro, const void* w, float* out) {
+int run_gemm_fused(spec_ctx* c, int which, ModelRt& m, const GemmPlan& p, GemmPro pro, const void* w, float* out) {
   const bool prof = (c->profile_flags & 1) && which == SPEC_TARGET;
-  hipEvent_t e0 = nullptr, e1 = nullptr;
   int rc;
-  if (prof && (rc = prof_events(c, (double)p.weight_bytes(), &e0, &e1))) return rc;
-  HIPCHK(launch_gemm_fused(p, pro, w, out, m.stream, which, e0, e1));
+  if (prof && (rc = prof_slot(c, (double)p.weight_bytes(), &pro.stamp))) return rc;
+  HIPCHK(launch_gemm_fused(p, pro, w, out, m.stream, which));
   return SPEC_OK;
 }
 
@@ -575,7 +580,7 @@ extern "C" void spec_free(spec_ctx* c) {
   if (c->res_host) (void)hipHostFree(c->res_host);
   for (int i = 0; i < SPEC_RING_MAX; ++i)
     if (c->ev_slot[i]) (void)hipEventDestroy(c->ev_slot[i]);
-  for (hipEvent_t e : c->prof.ev) (void)hipEventDestroy(e);
+  if (c->prof.dev) (void)hipFree(c->prof.dev);
   delete c;
 }
 
@@ -1273,16 +1278,27 @@ extern "C" int spec_set_profile(spec_ctx* c, int flags) {
 extern "C" int spec_profile_read(spec_ctx* c, double* ms_total, long long* n_launches, double* bytes_total) {
   if (!c || !ms_total || !n_launches || !bytes_total) FAIL(SPEC_E_INVAL, "null argument");
   HIPCHK(hipStreamSynchronize(c->m[0].stream));
+  ProfStamps& p = c->prof;
   double ms = 0.0;
-  for (size_t i = 0; i + 1 < c->prof.used; i += 2) {
-    float t = 0.f;
-    HIPCHK(hipEventElapsedTime(&t, c->prof.ev[i], c->prof.ev[i + 1]));
-    ms += t;
+  if (p.used) {
+    std::vector<unsigned long long> host((size_t)2 * STAMP_WAYS * p.used);
+    HIPCHK(hipMemcpy(host.data(), p.dev, host.size() * sizeof(unsigned long long), hipMemcpyDeviceToHost));
+    for (size_t i = 0; i < p.used; ++i) {
+      unsigned long long a = 0, b = 0;     // max of ~start = earliest start, max of end
+      for (int k = 0; k < STAMP_WAYS; ++k) {
+        const unsigned long long* s2 = &host[((size_t)i * STAMP_WAYS + k) * 2];
+        if (s2[0] > a) a = s2[0];
+        if (s2[1] > b) b = s2[1];
+      }
+      const unsigned long long t0 = ~a;
+      if (a && b > t0) ms += (double)(b - t0) * p.tick_s * 1e3;
+    }
+    HIPCHK(hipMemset(p.dev, 0, host.size() * sizeof(unsigned long long)));
   }
   *ms_total = ms;
-  *n_launches = (long long)(c->prof.used / 2);
-  *bytes_total = c->prof.bytes;
-  c->prof.used = 0;
-  c->prof.bytes = 0.0;
+  *n_launches = (long long)p.used;
+  *bytes_total = p.bytes;
+  p.used = 0;
+  p.bytes = 0.0;
   return SPEC_OK;
 }

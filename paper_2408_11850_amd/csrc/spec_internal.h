@@ -38,9 +38,9 @@ struct GemmPlan {
 // wgs_per_cu: 2 = fill both workgroup slots of every CU (a stream running alone), 1 = leave one slot to
 // the other stream's kernels.  The K split (S, spw) does not depend on it.
 GemmPlan gemm_plan(int M, int N, int K, int wgs_per_cu = 2);
-// ev0 / ev1: optional events that receive the kernel's own start / end time stamps
+// stamp: optional pair of device words that receives the launch's time stamps (see GemmPro::stamp)
 hipError_t launch_gemm_partials(const GemmPlan& p, const bf16* x, const void* wp, float* partials, hipStream_t st,
-                                int tag, hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr);
+                                int tag, unsigned long long* stamp = nullptr);
 
 // The RMSNorm of the decode path is split in three: the residual-add kernel stores x' = bf16(h * gain) and the
 // rows' sums of squares (W pieces per row); the projection runs on x' unchanged; whoever adds the projection's K
@@ -83,9 +83,16 @@ struct RowScale {
 // loads hide behind the start of the weight stream and three kernel boundaries per layer disappear.
 // ---------------------------------------------------------------------------------------
 enum { PRO_NONE = 0, PRO_ADDNORM = 1, PRO_SWIGLU = 2 };
+#define STAMP_WAYS 16
 #define GEMM_WAVES_PER_GROUP 8   // waves of a projection workgroup: a PRO_ADDNORM launch leaves 8 S sums of squares
 struct GemmPro {
   int kind;
+  // Optional time stamps of the launch (any kind): STAMP_WAYS pairs (workgroup b uses pair b % STAMP_WAYS, so that
+  // the atomics of a launch do not queue on one address: one pair cost 3.5 us per launch), stamp[2 i] = max over its
+  // workgroups of ~(start), stamp[2 i + 1] = max of their end, in ticks of the constant-rate wall clock; all start at
+  // 0.  The kernel's own duration, first workgroup in to last workgroup out, without the dispatch overhead that
+  // events around a launch include.
+  unsigned long long* stamp;
   // PRO_ADDNORM: x' = bf16((h_in + sum_s part[s]) * gain); the workgroups of the first panel range also store the new
   // residual stream to h_out (another buffer than h_in: the other workgroups still read h_in) and one sum of
   // squares per wave to ssq[0 .. 8 S)
@@ -101,7 +108,7 @@ struct GemmPro {
 };
 // the same projection for M = 1 with the activation formed in the prologue (pro.kind != PRO_NONE)
 hipError_t launch_gemm_fused(const GemmPlan& p, const GemmPro& pro, const void* wp, float* partials, hipStream_t st,
-                             int tag, hipEvent_t ev0 = nullptr, hipEvent_t ev1 = nullptr);
+                             int tag);
 
 
 // n = M * N elements; rs scales row i / N (N given) of the sum
