@@ -419,6 +419,11 @@ def main():
             tag = "" if a is None else f"_forced_alpha_{a}"
             side["pearl_without_pre_verify" + tag] = run(amd.ALGO_PEARL_NO_PRE, gamma, a)
             side["pearl_without_post_verify" + tag] = run(amd.ALGO_PEARL_NO_POST, gamma, a)
+        # pre-verify over guessed continuations (closing remark of Section 4.3): on random-init text the pool hardly
+        # ever guesses right, so this shows what the extra rows of the pre-verify forward cost, not what they can gain
+        for a in (None, 0.9):
+            tag = "" if a is None else f"_forced_alpha_{a}"
+            side["pearl_guessed_pre_verify" + tag] = run(amd.ALGO_PEARL_GUESS, gamma, a)
         log(f"[bench] side runs: {json.dumps(side, default=float)}")
 
     traffic = None

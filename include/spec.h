@@ -49,9 +49,13 @@ enum {
   SPEC_ACCEPT_SD = 1,   /* vanilla speculative decoding, Section 2: every row but the last tests a draft,
                            the last row draws the bonus token when all are accepted                      */
   SPEC_ACCEPT_PRE = 2,  /* pre-verify, Section 3.2 / Algorithm 2: row p = M_p(x) tests x_1          */
-  SPEC_ACCEPT_POST = 3  /* post-verify, Section 3.3 / Algorithm 2: every row tests a draft, no bonus.
+  SPEC_ACCEPT_POST = 3, /* post-verify, Section 3.3 / Algorithm 2: every row tests a draft, no bonus.
                            For SD and POST row 0 tests x_1, or x_2 when x_1 is already committed (it then
                            was the first token of the verify forward)                                    */
+  SPEC_ACCEPT_PRE_GUESS = 4 /* pre-verify of several draft tokens (closing remark of Section 4.3), after
+                           spec_verify_guess: row 0 = M_p(x) tests x_1; row i >= 1 = M_p(x + [g_1..g_i]) tests
+                           x_{i+1}, but only while the accepted drafts x_1..x_i are the guesses g_1..g_i - the
+                           first draft that leaves the guessed path ends the step without a rejection        */
 };
 enum { SPEC_MODE_PRE = 0, SPEC_MODE_POST = 1 };
 
@@ -128,6 +132,20 @@ int spec_draft_step(spec_ctx* ctx, float u, int32_t* tok_out_host);
  * fp32 logits [n_tokens][vocab] (tests only). */
 int spec_verify(spec_ctx* ctx, const int32_t* tokens_host, int n_tokens, float* logits_out_host);
 
+/* Pre-verify over guessed continuations - Section 4.3 ends with the remark that pre-verify could cover several
+ * draft tokens with the help of a candidate pool; the paper gives no algorithm, this is the library's reading of it.
+ * One target forward, asynchronous on the target stream, over the frontier x followed by guesses g_1..g_m of how
+ * the text goes on: row 0 is M_p(x) as in pre-verify (Section 3.2), row i is M_p(x + [g_1..g_i]).  If the draft
+ * model happens to draft x_1..x_i = g_1..g_i, row i is the target's exact distribution for x_{i+1}, so
+ * spec_accept(SPEC_ACCEPT_PRE_GUESS) can test several drafts with Eq. (1) in the pre-verify step; a wrong guess
+ * only wastes its row, the output distribution stays the target's.
+ * guess_host != NULL: n_guess tokens from the caller's candidate pool.  guess_host == NULL: the library's pool,
+ * the committed text itself as an n-gram cache - up to n_guess tokens that followed the most recent earlier
+ * occurrence of the frontier token (possibly none).  0 <= n_guess <= gamma_max - 1.  *n_fed (nullable) = guesses
+ * actually fed, i.e. the forward has *n_fed + 1 rows.  Needs fresh drafts (x_1 not yet committed), else
+ * SPEC_E_STATE.  logits_out_host as in spec_verify. */
+int spec_verify_guess(spec_ctx* ctx, const int32_t* guess_host, int n_guess, int* n_fed, float* logits_out_host);
+
 /* Speculative-sampling accept / reject on the device (Eq. (1): accept x iff r <= p[x]/q[x];
  * on the first rejection draw from norm(max(0, p - q)); Section 2 and Algorithm 2), then the
  * bookkeeping of the step.  Waits for both streams.  r_host[0..n_r-1] are the acceptance
@@ -137,6 +155,9 @@ int spec_verify(spec_ctx* ctx, const int32_t* tokens_host, int n_tokens, float* 
  * After the call the frontier is the last committed token.  *keep_len is -1 when the caches stay
  * as they are (drafts still pending), otherwise the caller must cut every cache that holds more
  * than *keep_len (= committed - 1) tokens back to that length with spec_rollback_kv.
+ * SPEC_ACCEPT_PRE_GUESS without a rejection commits the n >= 1 accepted drafts, keeps x_{n+1}.. pending (the next
+ * post-verify forward then has fewer rows: spec_pending_rows) and itself cuts the target cache back to committed - 1
+ * tokens (the guess rows behind the new frontier go; the draft cache stays): *keep_len is -1.
  * `force_mask`: < 0 = real decisions; otherwise bit i overrides the i-th decision (1 = accept)
  * - measurement and scripted tests only. */
 int spec_accept(spec_ctx* ctx, int kind, const float* r_host, int n_r, float u_resample, long long force_mask,
@@ -157,6 +178,9 @@ int spec_drop_drafts(spec_ctx* ctx);
 int spec_rewind(spec_ctx* ctx, int committed_len);
 
 int spec_kv_len(const spec_ctx* ctx, int which);     /* tokens currently in that model's cache */
+/* Rows of the next post-verify forward: the frontier (when it is the accepted draft x_1) plus the unverified
+ * drafts behind it.  gamma in Algorithm 2; 1..gamma after a pre-verify step over guesses; 0 with no drafts. */
+int spec_pending_rows(const spec_ctx* ctx);
 int spec_committed_len(const spec_ctx* ctx);         /* prompt + committed generated tokens    */
 int spec_kv_free_pages(const spec_ctx* ctx, int which);
 long long spec_forward_count(const spec_ctx* ctx, int which); /* forwards run so far by that model */
@@ -165,12 +189,16 @@ long long spec_forward_count(const spec_ctx* ctx, int which); /* forwards run so
  * speculative decoding (algo 1), autoregressive decoding (algo 0), and the two ablations of Section 4.3:
  * PEARL without pre-verify (algo 3: after a rejection one step only drafts, then the target verifies the frontier
  * and x_1..x_gamma while the draft goes on) and without post-verify (algo 4: x_1 is verified early, then the target
- * verifies x_2..x_gamma and draws a bonus token while the draft model idles).  Uniform arrays are indexed
+ * verifies x_2..x_gamma and draws a bonus token while the draft model idles).  algo 5 is PEARL whose pre-verify
+ * steps cover several draft tokens (spec_verify_guess with the library's pool, SPEC_OPT_GUESS_TOKENS guesses; with 0
+ * guesses it takes exactly the steps of algo 2); its post-verify step after such a step verifies what is left of
+ * the window (1..gamma rows).  Uniform arrays are indexed
  * by step: u_draft[t*gamma + i], r_accept[t*(gamma+1) + i], u_resample[t]; each must hold
  * n_generate steps (2 n_generate for algo 3, whose draft-only steps commit nothing).  The loop ends after n_generate tokens, or after max_steps steps if
  * max_steps > 0.  force_bits == NULL uses real decisions; otherwise decision (t, i) is taken
  * from force_bits[t*(gamma+1)+i] (measurement only).  SPEC_E_STATE if drafts of an earlier call are still
- * pending that this loop cannot take over (any for algo 0 / 1; a number other than gamma for the PEARL variants).
+ * pending that this loop cannot take over (any for algo 0 / 1; a number other than gamma for the PEARL variants,
+ * more than gamma for algo 5).
  * out_tokens_host receives the committed
  * tokens (at most n_generate; stats[1] tells how many were committed).
  * stats_host (nullable, 8 doubles): steps, committed, draft forwards, target forwards,
@@ -272,12 +300,14 @@ int spec_accept_rows_static(const float* p_logits_dev, int n_rows, const float* 
  * prologue (residual add + norm input, SiLU * mul); 0 = the ten-kernel chain that forwards over several tokens use.
  * Same operations, sums in the same order up to the grouping of the sums of squares (results agree to fp32
  * rounding, not bit for bit).
+ * SPEC_OPT_GUESS_TOKENS: most guesses k a pre-verify step of algo 5 feeds behind the frontier; -1 (default) =
+ * gamma - 1, the most that can be used; values above gamma - 1 are clipped.
  * SPEC_OPT_TEST_FAIL_PREFILL (tests of the error path only): n > 0 makes the next spec_prefill give up with
  * SPEC_E_NOMEM after its n-th forward, as if the KV pages had run out half way; one-shot.
  * spec_get_option reads a value back; for SPEC_OPT_GEMM_WGS_PER_CU it is the mode the next forward launches with
  * (1 or 2). */
 enum { SPEC_OPT_GEMM_WGS_PER_CU = 1, SPEC_OPT_GRAPHS = 2, SPEC_OPT_PREFILL = 3, SPEC_OPT_TEST_FAIL_PREFILL = 4,
-       SPEC_OPT_FUSE_SINGLE = 5 };
+       SPEC_OPT_FUSE_SINGLE = 5, SPEC_OPT_GUESS_TOKENS = 6 };
 int spec_set_option(spec_ctx* ctx, int option, int value);
 int spec_get_option(const spec_ctx* ctx, int option, int* value);
 

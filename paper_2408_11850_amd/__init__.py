@@ -14,17 +14,19 @@ LIB_PATH = os.path.join(_HERE, "libspec.so")
 
 SPEC_OK, SPEC_E_INVAL, SPEC_E_NOMEM, SPEC_E_STATE, SPEC_E_HIP = 0, -1, -2, -3, -4
 SPEC_TARGET, SPEC_DRAFT = 0, 1
-SPEC_ACCEPT_AR, SPEC_ACCEPT_SD, SPEC_ACCEPT_PRE, SPEC_ACCEPT_POST = 0, 1, 2, 3
+SPEC_ACCEPT_AR, SPEC_ACCEPT_SD, SPEC_ACCEPT_PRE, SPEC_ACCEPT_POST, SPEC_ACCEPT_PRE_GUESS = 0, 1, 2, 3, 4
 SPEC_MODE_PRE, SPEC_MODE_POST = 0, 1
 SPEC_MAX_TOKENS = 32
 PAGE_TOKENS = 64
 ALGO_AR, ALGO_SD, ALGO_PEARL = 0, 1, 2
 ALGO_PEARL_NO_PRE, ALGO_PEARL_NO_POST = 3, 4      # the two ablations
+ALGO_PEARL_GUESS = 5                               # pre-verify steps cover several draft tokens (Section 4.3, closing remark)
 SPEC_OPT_GEMM_WGS_PER_CU = 1
 SPEC_OPT_GRAPHS = 2
 SPEC_OPT_PREFILL = 3
 SPEC_OPT_TEST_FAIL_PREFILL = 4
 SPEC_OPT_FUSE_SINGLE = 5
+SPEC_OPT_GUESS_TOKENS = 6
 EPI_STORE, EPI_RESID, EPI_SWIGLU = 0, 1, 2
 
 
@@ -59,11 +61,13 @@ SIGNATURES = {
     "spec_prefill": (C.c_int, [_P, _PI32, C.c_int, C.c_int]),
     "spec_draft_step": (C.c_int, [_P, C.c_float, _PI32]),
     "spec_verify": (C.c_int, [_P, _PI32, C.c_int, _PF]),
+    "spec_verify_guess": (C.c_int, [_P, _PI32, C.c_int, _PI, _PF]),
     "spec_accept": (C.c_int, [_P, C.c_int, _PF, C.c_int, C.c_float, C.c_longlong, _PI, _PI32, _PI, _PI, _PI]),
     "spec_rollback_kv": (C.c_int, [_P, C.c_int, C.c_int]),
     "spec_drop_drafts": (C.c_int, [_P]),
     "spec_rewind": (C.c_int, [_P, C.c_int]),
     "spec_kv_len": (C.c_int, [_P, C.c_int]),
+    "spec_pending_rows": (C.c_int, [_P]),
     "spec_committed_len": (C.c_int, [_P]),
     "spec_kv_free_pages": (C.c_int, [_P, C.c_int]),
     "spec_forward_count": (C.c_longlong, [_P, C.c_int]),

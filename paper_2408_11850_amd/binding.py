@@ -196,6 +196,24 @@ class SpecContext:
         check(self.lib.spec_verify(self._ctx, tp, n, lp))
         return logits
 
+    def verify_guess(self, guess=None, n_guess: int = 0, want_logits: bool = False):
+        """Target forward over the frontier and guessed continuations (pre-verify of several draft tokens).  `guess`:
+        the caller's tokens, or None for up to n_guess tokens of the library's own pool.  Returns (guesses fed, logits
+        [fed + 1, vocab] or None)."""
+        if guess is not None:
+            arr = np.ascontiguousarray(np.asarray(guess, dtype=np.int32))
+            n, gp = len(arr), arr.ctypes.data_as(C.POINTER(C.c_int32))
+        else:
+            n, gp = int(n_guess), None
+        logits = np.empty((n + 1, self.vocab), dtype=np.float32) if want_logits else None
+        lp = logits.ctypes.data_as(C.POINTER(C.c_float)) if want_logits else None
+        fed = C.c_int(-1)
+        check(self.lib.spec_verify_guess(self._ctx, gp, n, C.byref(fed), lp))
+        return fed.value, (logits[:fed.value + 1] if want_logits else None)
+
+    def pending_rows(self) -> int:
+        return check(self.lib.spec_pending_rows(self._ctx))
+
     def accept(self, kind: int, r=(), u_resample: float = 0.5, force_mask: int = -1):
         r = np.ascontiguousarray(np.asarray(r, dtype=np.float32))
         n_acc, n_out, mode, keep = C.c_int(), C.c_int(), C.c_int(), C.c_int()

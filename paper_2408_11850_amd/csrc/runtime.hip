@@ -93,6 +93,9 @@ struct spec_ctx {
   int ring_base = 0, n_drafted = 0;
   bool first_verified = false;    // x_1 of the ring is already committed (it is the frontier)
   int last_verify_rows = 0;
+  int n_guess = -1;               // >= 0: the last target forward was spec_verify_guess over the frontier + guess[0..n_guess)
+  int guess[SPEC_MAX_TOKENS];
+  int guess_opt = -1;             // most guesses per pre-verify step of the loop: -1 = gamma - 1
   bool prefilled = false;
   int mode = SPEC_MODE_PRE;       // strategy of the next PEARL step
   int profile_flags = 0;
@@ -609,6 +612,7 @@ extern "C" int spec_prefill(spec_ctx* c, const int32_t* prompt, int n_prompt, in
   c->committed.assign(prompt, prompt + n_prompt);
   c->n_prompt = n_prompt;
   c->last_verify_rows = 0;
+  c->n_guess = -1;
   c->mode = SPEC_MODE_PRE;
   int fail_after = c->fail_prefill_after;   // one-shot test hook (SPEC_OPT_TEST_FAIL_PREFILL)
   c->fail_prefill_after = 0;
@@ -723,9 +727,61 @@ extern "C" int spec_verify(spec_ctx* c, const int32_t* tokens, int n_tokens, flo
   int rc = forward(c, SPEC_TARGET, src, n_tokens);
   if (rc) return rc;
   c->last_verify_rows = n_tokens;
+  c->n_guess = -1;
   if (logits_out) {
     HIPCHK(hipStreamSynchronize(m.stream));
     HIPCHK(hipMemcpy(logits_out, m.logits, (size_t)n_tokens * m.d.vocab * sizeof(float), hipMemcpyDeviceToHost));
+  }
+  return SPEC_OK;
+}
+
+// The library's candidate pool: the committed text as an n-gram cache.  Writes up to k tokens that followed the
+// most recent earlier occurrence of the frontier token; returns how many (0 if the token has not occurred before).
+static int pool_guesses(const std::vector<int>& text, int k, int* out) {
+  const int n = (int)text.size();
+  if (k <= 0 || n < 2) return 0;
+  const int frontier = text[n - 1];
+  int at = n - 2;
+  while (at >= 0 && text[at] != frontier) --at;
+  if (at < 0) return 0;
+  int m = 0;
+  for (int j = at + 1; j < n && m < k; ++j) out[m++] = text[j];
+  return m;
+}
+
+extern "C" int spec_verify_guess(spec_ctx* c, const int32_t* guess, int n_guess, int* n_fed, float* logits_out) {
+  if (!c) FAIL(SPEC_E_INVAL, "null context");
+  if (!c->prefilled) FAIL(SPEC_E_STATE, "spec_prefill has not run");
+  if (n_guess < 0 || n_guess > c->cfg.gamma_max - 1) FAIL(SPEC_E_INVAL, "n_guess outside 0..gamma_max-1 = %d", c->cfg.gamma_max - 1);
+  ModelRt& m = c->m[SPEC_TARGET];
+  if (c->first_verified) FAIL(SPEC_E_STATE, "pre-verify needs fresh drafts, but x_1 is already committed");
+  if (m.len != (int)c->committed.size() - 1)
+    FAIL(SPEC_E_STATE, "target cache holds %d tokens, expected %zu", m.len, c->committed.size() - 1);
+  int g[SPEC_MAX_TOKENS];
+  int ng = 0;
+  if (guess) {
+    for (int i = 0; i < n_guess; ++i) {
+      if (guess[i] < 0 || guess[i] >= m.d.vocab) FAIL(SPEC_E_INVAL, "guess[%d] outside the vocabulary", i);
+      g[i] = guess[i];
+    }
+    ng = n_guess;
+  } else {
+    ng = pool_guesses(c->committed, n_guess, g);
+  }
+  TokenSrc src;
+  src.n = ng + 1;
+  src.imm[0] = c->committed.back();
+  src.slot[0] = 0;
+  for (int i = 0; i < ng; ++i) src.imm[1 + i] = g[i], src.slot[1 + i] = 0;
+  int rc = forward(c, SPEC_TARGET, src, ng + 1);
+  if (rc) return rc;
+  c->last_verify_rows = ng + 1;
+  c->n_guess = ng;
+  for (int i = 0; i < ng; ++i) c->guess[i] = g[i];
+  if (n_fed) *n_fed = ng;
+  if (logits_out) {
+    HIPCHK(hipStreamSynchronize(m.stream));
+    HIPCHK(hipMemcpy(logits_out, m.logits, (size_t)(ng + 1) * m.d.vocab * sizeof(float), hipMemcpyDeviceToHost));
   }
   return SPEC_OK;
 }
@@ -748,10 +804,18 @@ extern "C" int spec_accept(spec_ctx* c, int kind, const float* r, int n_r, float
     case SPEC_ACCEPT_SD: a.n_test = c->last_verify_rows - 1; break;    // the last row draws the bonus token
     case SPEC_ACCEPT_PRE: a.n_test = 1; break;
     case SPEC_ACCEPT_POST: a.n_test = c->last_verify_rows; break;      // every row tests a draft, no bonus
+    case SPEC_ACCEPT_PRE_GUESS: a.n_test = c->last_verify_rows; break; // row i tests x_{i+1} while the drafts follow the guesses
     default: FAIL(SPEC_E_INVAL, "unknown accept kind %d", kind);
   }
   if (c->last_verify_rows < 1) FAIL(SPEC_E_STATE, "no target forward to accept against");
   if (kind == SPEC_ACCEPT_PRE && c->last_verify_rows != 1) FAIL(SPEC_E_STATE, "pre-verify needs a one-token target forward");
+  if (kind == SPEC_ACCEPT_PRE_GUESS) {
+    if (c->n_guess < 0 || c->last_verify_rows != c->n_guess + 1)
+      FAIL(SPEC_E_STATE, "pre-verify over guesses needs the target forward of spec_verify_guess");
+    if (c->first_verified) FAIL(SPEC_E_STATE, "pre-verify needs fresh drafts, but x_1 is already committed");
+    a.guided = 1;
+    for (int i = 0; i < c->n_guess; ++i) a.guess[i] = c->guess[i];
+  }
   if (kind == SPEC_ACCEPT_PRE && c->first_verified) FAIL(SPEC_E_STATE, "pre-verify needs fresh drafts, but x_1 is already committed");
   if (first + a.n_test - 1 > c->n_drafted) FAIL(SPEC_E_STATE, "%d drafts to test, %d drafted", a.n_test, c->n_drafted);
   if (a.n_test > 0 && (!r || n_r < a.n_test)) FAIL(SPEC_E_INVAL, "%d acceptance uniforms needed", a.n_test);
@@ -772,6 +836,8 @@ extern "C" int spec_accept(spec_ctx* c, int kind, const float* r, int n_r, float
   int no = 0;
   *keep_len = -1;
   c->last_verify_rows = 0;
+  c->n_guess = -1;
+  bool cut_target = false;
   switch (kind) {
     case SPEC_ACCEPT_AR:
       tokens_out[no++] = res.token;
@@ -809,8 +875,27 @@ extern "C" int spec_accept(spec_ctx* c, int kind, const float* r, int n_r, float
         *next_mode = SPEC_MODE_PRE;
       }
       break;
+    case SPEC_ACCEPT_PRE_GUESS:
+      for (int i = 0; i < n; ++i) tokens_out[no++] = res.ring[a.slot[i]];
+      if (res.rejected) {
+        tokens_out[no++] = res.token;
+        reset_ring(c);
+        *next_mode = SPEC_MODE_PRE;
+      } else {
+        // x_n (n >= 1: row 0 always tests x_1) is the new frontier and becomes x_1; x_{n+1}.. stay pending
+        c->ring_base = (c->ring_base + n - 1) % c->ring_n;
+        c->n_drafted -= n - 1;
+        c->first_verified = true;
+        cut_target = true;   // the guess rows behind the new frontier leave the target cache
+        *next_mode = SPEC_MODE_POST;
+      }
+      break;
   }
   for (int i = 0; i < no; ++i) c->committed.push_back(tokens_out[i]);
+  if (cut_target && mt.len > (int)c->committed.size() - 1) {
+    int rc = rollback_model(c, SPEC_TARGET, (int)c->committed.size() - 1);
+    if (rc) return rc;
+  }
   if (kind == SPEC_ACCEPT_SD || res.rejected) *keep_len = (int)c->committed.size() - 1;
   *n_accepted = n;
   *n_out = no;
@@ -839,6 +924,7 @@ extern "C" int spec_rewind(spec_ctx* c, int committed_len) {
   reset_ring(c);
   c->mode = SPEC_MODE_PRE;
   c->last_verify_rows = 0;
+  c->n_guess = -1;
   for (int w = 0; w < 2; ++w)
     if (c->m[w].len > committed_len - 1) {
       int rc = rollback_model(c, w, committed_len - 1);
@@ -850,6 +936,11 @@ extern "C" int spec_rewind(spec_ctx* c, int committed_len) {
 extern "C" int spec_kv_len(const spec_ctx* c, int which) {
   if (!c || (which != SPEC_TARGET && which != SPEC_DRAFT)) return SPEC_E_INVAL;
   return c->m[which].len;
+}
+extern "C" int spec_pending_rows(const spec_ctx* c) {
+  if (!c) return SPEC_E_INVAL;
+  if (c->n_drafted == 0) return 0;
+  return c->first_verified ? c->n_drafted : c->n_drafted + 1;
 }
 extern "C" int spec_committed_len(const spec_ctx* c) { return c ? (int)c->committed.size() : SPEC_E_INVAL; }
 extern "C" int spec_kv_free_pages(const spec_ctx* c, int which) {
@@ -868,8 +959,9 @@ extern "C" int spec_generate(spec_ctx* c, int algo, int gamma, int n_generate, i
                              const float* r_accept, const float* u_resample, const uint8_t* force_bits,
                              int32_t* out_tokens, double* stats) {
   if (!c || !out_tokens || !u_resample) FAIL(SPEC_E_INVAL, "null argument");
-  if (algo < 0 || algo > 4)
-    FAIL(SPEC_E_INVAL, "algo must be 0 (AR), 1 (SD), 2 (PEARL), 3 (PEARL w/o pre-verify) or 4 (PEARL w/o post-verify)");
+  if (algo < 0 || algo > 5)
+    FAIL(SPEC_E_INVAL, "algo must be 0 (AR), 1 (SD), 2 (PEARL), 3 (PEARL w/o pre-verify), 4 (PEARL w/o post-verify) or "
+                       "5 (PEARL with pre-verify over guesses)");
   if (algo > 0 && (gamma < 1 || gamma > c->cfg.gamma_max || !u_draft || !r_accept)) FAIL(SPEC_E_INVAL, "bad gamma / uniforms");
   if (n_generate < 1) FAIL(SPEC_E_INVAL, "n_generate must be positive");
   if (!c->prefilled) FAIL(SPEC_E_STATE, "spec_prefill has not run");
@@ -878,8 +970,12 @@ extern "C" int spec_generate(spec_ctx* c, int algo, int gamma, int n_generate, i
   if (algo <= 1 && c->n_drafted > 0)
     FAIL(SPEC_E_STATE, "%d unverified drafts pending: drop them (spec_drop_drafts + spec_rollback_kv, or spec_rewind) first",
          c->n_drafted);
-  if (algo >= 2 && c->n_drafted != 0 && c->n_drafted != gamma)
+  if (algo >= 2 && algo != 5 && c->n_drafted != 0 && c->n_drafted != gamma)
     FAIL(SPEC_E_STATE, "%d unverified drafts pending do not fit a window of %d", c->n_drafted, gamma);
+  // pre-verify over guesses leaves 1..gamma drafts pending, the first of them committed
+  if (algo == 5 && c->n_drafted != 0 && (c->n_drafted > gamma || !c->first_verified))
+    FAIL(SPEC_E_STATE, "%d unverified drafts pending do not fit a window of %d", c->n_drafted, gamma);
+  const int k_guess = (c->guess_opt < 0 || c->guess_opt > gamma - 1) ? gamma - 1 : c->guess_opt;
   const int g1 = gamma + 1;
   // the launch mode is put back on every way out of the loop, errors included
   struct WgsGuard {
@@ -933,6 +1029,22 @@ extern "C" int spec_generate(spec_ctx* c, int algo, int gamma, int n_generate, i
       n_test = gamma - 1;
       post_steps++;
       if ((rc = spec_verify(c, nullptr, gamma, nullptr))) return rc;
+    } else if (algo == 5 && mode == SPEC_MODE_PRE) {
+      // pre-verify over the frontier and up to k guessed tokens (closing remark of Section 4.3)
+      kind = SPEC_ACCEPT_PRE_GUESS;
+      int fed = 0;
+      if ((rc = spec_verify_guess(c, nullptr, k_guess, &fed, nullptr))) return rc;
+      n_test = fed + 1;
+      for (int i = 0; i < gamma; ++i)
+        if ((rc = spec_draft_step(c, u_draft[t * gamma + i], nullptr))) return rc;
+    } else if (algo == 5) {
+      // post-verify of what the pre-verify step left of the window: the frontier x_1 and the drafts behind it
+      kind = SPEC_ACCEPT_POST;
+      n_test = c->n_drafted;
+      post_steps++;
+      if ((rc = spec_verify(c, nullptr, n_test, nullptr))) return rc;
+      for (int i = 0; i < gamma; ++i)
+        if ((rc = spec_draft_step(c, u_draft[t * gamma + i], nullptr))) return rc;
     } else if (mode == SPEC_MODE_PRE) {
       kind = SPEC_ACCEPT_PRE;
       n_test = 1;
@@ -961,8 +1073,10 @@ extern "C" int spec_generate(spec_ctx* c, int algo, int gamma, int n_generate, i
         if (len > keep && (rc = rollback_model(c, w, keep))) return rc;
       }
     accepted += n_acc;
-    // tokens actually tested: up to and including the first rejection
-    tested += (n_acc < n_test) ? n_acc + 1 : n_test;
+    // tokens actually tested: up to and including the first rejection (a pre-verify over guesses may stop earlier
+    // without one: keep >= 0 tells a rejection there)
+    if (kind == SPEC_ACCEPT_PRE_GUESS) tested += n_acc + (keep >= 0 ? 1 : 0);
+    else tested += (n_acc < n_test) ? n_acc + 1 : n_test;
     produced += n_out;
     mode = next_mode;
     steps++;
@@ -1249,6 +1363,11 @@ extern "C" int spec_set_option(spec_ctx* c, int option, int value) {
     c->prefill_opt = value;
     return SPEC_OK;
   }
+  if (option == SPEC_OPT_GUESS_TOKENS) {
+    if (value < -1 || value > SPEC_MAX_TOKENS - 2) FAIL(SPEC_E_INVAL, "SPEC_OPT_GUESS_TOKENS takes -1 or 0..%d", SPEC_MAX_TOKENS - 2);
+    c->guess_opt = value;
+    return SPEC_OK;
+  }
   if (option == SPEC_OPT_TEST_FAIL_PREFILL) {
     if (value < 0) FAIL(SPEC_E_INVAL, "SPEC_OPT_TEST_FAIL_PREFILL takes a count >= 0");
     c->fail_prefill_after = value;
@@ -1265,6 +1384,7 @@ extern "C" int spec_get_option(const spec_ctx* c, int option, int* value) {
     case SPEC_OPT_PREFILL: *value = c->prefill_opt; return SPEC_OK;
     case SPEC_OPT_FUSE_SINGLE: *value = c->fuse_single ? 1 : 0; return SPEC_OK;
     case SPEC_OPT_TEST_FAIL_PREFILL: *value = c->fail_prefill_after; return SPEC_OK;
+    case SPEC_OPT_GUESS_TOKENS: *value = c->guess_opt; return SPEC_OK;
   }
   FAIL(SPEC_E_INVAL, "unknown option %d", option);
 }

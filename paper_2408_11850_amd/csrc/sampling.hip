@@ -389,10 +389,18 @@ __global__ __launch_bounds__(SAMP_THREADS) void accept_finish_kernel(const float
   __shared__ int shi[2];
   __shared__ double rt[SAMP_WAVES][SAMP_ROWS_MAX + 1];
   int n = 0;
-  while (n < a.n_test && __float_as_int(stats[n * 4 + 3]) != 0) ++n;
-  const bool rejected = n < a.n_test;
+  bool off_path = false;   // guided tests: row n is the target's distribution after x_1..x_n only if those are the guesses
+  while (n < a.n_test) {
+    if (a.guided && n >= 1 && ring[a.slot[n - 1]] != a.guess[n - 1]) {
+      off_path = true;
+      break;
+    }
+    if (__float_as_int(stats[n * 4 + 3]) == 0) break;
+    ++n;
+  }
+  const bool rejected = !off_path && n < a.n_test;
   int token = -1;
-  if (rejected || n < a.n_rows) {   // a row to draw from exists: the rejecting row, or the bonus row
+  if (rejected || (!a.guided && n < a.n_rows)) {   // a row to draw from exists: the rejecting row, or the bonus row
     const float* row = logits + (size_t)n * V;
     const float vmax = stats[n * 4 + 0], sum = stats[n * 4 + 1];
     const int amax = __float_as_int(stats[n * 4 + 2]);
@@ -450,7 +458,7 @@ __global__ __launch_bounds__(SAMP_THREADS) void accept_finish_kernel(const float
     res->n_accepted = n;
     res->token = token;
     res->rejected = rejected ? 1 : 0;
-    res->pad = 0;
+    res->off_path = off_path ? 1 : 0;
     if (out2) {   // callers that want the outcome in device memory of their own
       out2[0] = n;
       out2[1] = token;
@@ -463,6 +471,7 @@ hipError_t launch_accept(const float* logits, int V, float mult, int greedy, con
                          const int* x_direct, AcceptArgs a, float* stats_scratch, AcceptResult* result_dev,
                          hipStream_t st, int* out2) {
   // stats_scratch: 4 floats per row, followed (at a 256-float offset) by one scratch row of V floats
+  if (a.guided && !ring) return hipErrorInvalidValue;   // guided tests compare ring tokens with the guesses
   accept_rows_kernel<<<a.n_rows, SAMP_THREADS, 0, st>>>(logits, V, mult, greedy, qcache, ring, x_direct, a,
                                                         stats_scratch);
   hipError_t e = hipGetLastError();

@@ -187,12 +187,14 @@ struct AcceptArgs {
   float r[SPEC_MAX_TOKENS];
   float u_resample;
   long long force_mask;     // < 0: none
+  int guided;               // 1: row i >= 1 exists only if the drafts tested by rows 0..i-1 equal guess[0..i-1]; no bonus row
+  int guess[SPEC_MAX_TOKENS];
 };
 struct AcceptResult {       // device -> pinned host
   int n_accepted;
   int token;                // corrected / bonus / autoregressive token, -1 if none
   int rejected;             // 1 if a rejection happened
-  int pad;
+  int off_path;             // 1 if a guided test ended at a draft that left the guessed path (no rejection)
   int ring[SPEC_RING_MAX];  // snapshot of the draft-token ring
 };
 hipError_t launch_sample_row(const float* logits, int V, float mult, int greedy, float u, float* q_out, int* tok_out,

@@ -131,12 +131,14 @@ def test_sampled_loops_follow_the_oracle_step_by_step(algo, gamma, temperature):
 
 def lockstep_run(amd, harness, cfg, target, draft, tm, dm, algo, gamma, temperature, n_total, seed, oracle_loop=None,
                  gpu_steps=None, prompt=None, prefill_mode=-1, uniform_rows=1, check_forward=True, first_segment=24,
-                 oracle_caches=None):
+                 oracle_caches=None, gpu_first=False):
     """One loop of the library against the oracle's loop fed with the library's own logits (LockstepModel): every
     forward of the run is compared with the fp32 oracle forward, every decision must be the oracle's.  Returns
     (steps compared, splits, worst logit error of the target, of the draft, modes seen).
     oracle_caches: optional (target, draft) oracle CachedModels that already hold prompt[:-1] (first segment only;
-    saves a second prompt pass on the CPU where the prompt is long)."""
+    saves a second prompt pass on the CPU where the prompt is long).
+    gpu_first: run the library's loop of a segment before the oracle's (for hooks that hand what the library's loop
+    fed, e.g. scripted guesses, to the oracle's loop; the two run on separate contexts, so the order changes nothing)."""
     if prompt is None:
         prompt = synth.prompt_tokens(cfg.n_prompt, cfg.target.vocab, cfg.seed_prompt).tolist()
     prompt = list(prompt)
@@ -162,6 +164,9 @@ def lockstep_run(amd, harness, cfg, target, draft, tm, dm, algo, gamma, temperat
             ld = LockstepModel(src_d, ocm(dm)).begin(prompt)
         kw = dict(temperature=temperature, logit_scale=cfg.logit_scale)
         ref = []
+        if gpu_first:
+            ctx.prefill(prompt)
+            got = (gpu_steps or _gpu_steps)(amd, ctx, algo, gamma, seg_len, uni)
         if oracle_loop is not None:
             oracle_loop(lt, ld, prompt, seg_len, gamma, uni, trace=ref, **kw)
         elif algo == 0:
@@ -173,8 +178,9 @@ def lockstep_run(amd, harness, cfg, target, draft, tm, dm, algo, gamma, temperat
         else:
             loops.pearl(lt, ld, prompt, seg_len, gamma, uni, trace=ref, **kw)
         worst_t, worst_d = max(worst_t, lt.worst), max(worst_d, ld.worst)
-        ctx.prefill(prompt)
-        got = (gpu_steps or _gpu_steps)(amd, ctx, algo, gamma, seg_len, uni)
+        if not gpu_first:
+            ctx.prefill(prompt)
+            got = (gpu_steps or _gpu_steps)(amd, ctx, algo, gamma, seg_len, uni)
         k = 0
         while k < min(len(ref), len(got)) and ref[k]["tokens"] == got[k]["tokens"]:
             modes.add(ref[k].get("mode"))
