@@ -100,6 +100,46 @@ def silu(x):
     return x / (1.0 + np.exp(-x))
 
 
+def layer_forward(model: Model, cache: KVCache, l: int, w: dict, h, n: int):
+    """One decoder layer over the M rows of h (the tokens at positions n .. n+M-1): appends their keys / values to
+    layer l of the cache (cache.len is not moved) and returns the new residual stream.  `w`: the layer's matrices
+    and gains as arrays of model.dtype.  forward() is embedding -> this for every layer -> head(); it is a function
+    of its own so that a test can hand over a deep model's layers one at a time."""
+    M = h.shape[0]
+    H, Hkv, D = model.n_heads, model.n_kv_heads, model.head_dim
+    group = H // Hkv
+    pos = np.arange(n, n + M)
+    scale = model.dtype(1.0 / np.sqrt(D))
+    rb = bf16_round if model.act_bf16 else (lambda x: x)
+    a, sc = norm_input(model, h, w["attn_norm"])
+    q = ((a @ w["wq"].T) * sc).reshape(M, H, D)
+    k = ((a @ w["wk"].T) * sc).reshape(M, Hkv, D)
+    v = rb(((a @ w["wv"].T) * sc).reshape(M, Hkv, D))
+    q = rb(rope(q, pos, model.rope_theta))
+    k = rb(rope(k, pos, model.rope_theta))
+    cache.k[l, n:n + M] = k
+    cache.v[l, n:n + M] = v
+    o = np.zeros((M, H, D), dtype=model.dtype)
+    for i in range(M):
+        T = n + i + 1                                          # token i sees positions 0..n+i
+        for j in range(H):
+            kv = j // group
+            s = (cache.k[l, :T, kv] @ q[i, j]) * scale        # [T]
+            s = s - s.max()
+            p = np.exp(s)
+            o[i, j] = (rb(p) @ cache.v[l, :T, kv]) / p.sum()   # = softmax(s) @ V; the weights on V rounded if asked
+    h = h + rb(o.reshape(M, H * D)) @ w["wo"].T
+    b, sc = norm_input(model, h, w["ffn_norm"])
+    z = rb(silu((b @ w["w_gate"].T) * sc) * ((b @ w["w_up"].T) * sc))
+    return h + z @ w["w_down"].T
+
+
+def head(model: Model, h) -> np.ndarray:
+    """Final norm and LM head: logits [M, vocab] of the rows of h."""
+    a, sc = norm_input(model, h, model.final_norm)
+    return (a @ model.lm_head.T) * sc
+
+
 def forward(model: Model, cache: KVCache, tokens) -> np.ndarray:
     """Feed M new tokens at positions cache.len .. cache.len+M-1; return logits [M, vocab].
 
@@ -111,37 +151,11 @@ def forward(model: Model, cache: KVCache, tokens) -> np.ndarray:
     n = cache.len
     if n + M > cache.k.shape[1]:
         raise ValueError("KV cache overflow")
-    H, Hkv, D = model.n_heads, model.n_kv_heads, model.head_dim
-    group = H // Hkv
-    pos = np.arange(n, n + M)
-    scale = model.dtype(1.0 / np.sqrt(D))
-    rb = bf16_round if model.act_bf16 else (lambda x: x)
     h = model.tok_embed[tokens]                                   # [M, d]
     for l, w in enumerate(model.layers):
-        a, sc = norm_input(model, h, w["attn_norm"])
-        q = ((a @ w["wq"].T) * sc).reshape(M, H, D)
-        k = ((a @ w["wk"].T) * sc).reshape(M, Hkv, D)
-        v = rb(((a @ w["wv"].T) * sc).reshape(M, Hkv, D))
-        q = rb(rope(q, pos, model.rope_theta))
-        k = rb(rope(k, pos, model.rope_theta))
-        cache.k[l, n:n + M] = k
-        cache.v[l, n:n + M] = v
-        o = np.zeros((M, H, D), dtype=model.dtype)
-        for i in range(M):
-            T = n + i + 1                                          # token i sees positions 0..n+i
-            for j in range(H):
-                kv = j // group
-                s = (cache.k[l, :T, kv] @ q[i, j]) * scale        # [T]
-                s = s - s.max()
-                p = np.exp(s)
-                o[i, j] = (rb(p) @ cache.v[l, :T, kv]) / p.sum()   # = softmax(s) @ V; the weights on V rounded if asked
-        h = h + rb(o.reshape(M, H * D)) @ w["wo"].T
-        b, sc = norm_input(model, h, w["ffn_norm"])
-        z = rb(silu((b @ w["w_gate"].T) * sc) * ((b @ w["w_up"].T) * sc))
-        h = h + z @ w["w_down"].T
+        h = layer_forward(model, cache, l, w, h, n)
     cache.len = n + M
-    a, sc = norm_input(model, h, model.final_norm)
-    return (a @ model.lm_head.T) * sc
+    return head(model, h)
 
 
 class CachedModel:
