@@ -278,29 +278,15 @@ def _np_layer(shape, seed, l):
     return lay
 
 
-def test_full_depth_target_against_the_oracle_layer_by_layer(full_depth_pair):
-    """The 80-layer 70B-shape target itself against the oracle.  The fp32 oracle cannot hold 70e9 weights at once,
-    but it can take them one layer at a time: the test generates layer l again (same generator, same seeds), runs
-    oracle.transformer.layer_forward for the plain fp32 oracle and for the oracle with bf16 activations, and drops
-    the layer.  One causal pass over the whole sequence (32 prompt tokens, the frontier, 7 more tokens) gives the
-    oracle's logits of the rows the library then computes as a one-token and a seven-token verify forward - after
-    either prompt path.  In a random-init network of these widths bf16 activation rounding grows with depth (the
-    two oracles part by eoo, no library involved); the library must be no further from the fp32 oracle than that,
-    within a factor - a mistake in any layer (a wrong gain vector, a misplaced head, a stale cache row) gives errors
-    of the order of the logit range itself."""
+def _streamed_oracle_logits(shape, seed, seq):
+    """Logits [len(seq), vocab] of one causal pass over `seq` from the plain fp32 oracle and from the oracle with
+    bf16 activations, the layers generated, used by both and dropped one at a time."""
     import torch
-    amd, harness, cfg, target, draft = full_depth_pair
-    shape = cfg.target
-    prompt = synth.prompt_tokens(33, shape.vocab, 41).tolist()
-    extra = synth.prompt_tokens(7, shape.vocab, 42).tolist()
-    seq = prompt + extra
     cv = lambda t: np.ascontiguousarray(t.float().cpu().numpy())
-    glob = {"tok_embed": cv(synth.normal_tensor((shape.vocab, shape.d_model), 0.02, cfg.seed_target,
-                                                synth._GLOBAL["tok_embed"], torch.bfloat16, "cuda")),
-            "lm_head": cv(synth.normal_tensor((shape.vocab, shape.d_model), 0.02, cfg.seed_target,
-                                              synth._GLOBAL["lm_head"], torch.bfloat16, "cuda")),
-            "final_norm": cv(synth.gain_tensor(shape.d_model, cfg.seed_target, synth._GLOBAL["final_norm"],
-                                               torch.bfloat16, "cuda")),
+    gen = lambda name: synth.normal_tensor((shape.vocab, shape.d_model), 0.02, seed, synth._GLOBAL[name],
+                                           torch.bfloat16, "cuda")
+    glob = {"tok_embed": cv(gen("tok_embed")), "lm_head": cv(gen("lm_head")),
+            "final_norm": cv(synth.gain_tensor(shape.d_model, seed, synth._GLOBAL["final_norm"], torch.bfloat16, "cuda")),
             "layers": []}
     models, caches, hs = [], [], []
     for act_bf16 in (False, True):
@@ -308,10 +294,10 @@ def test_full_depth_target_against_the_oracle_layer_by_layer(full_depth_pair):
                               act_bf16=act_bf16)
         m.layers = [None] * shape.n_layers          # the cache is sized from this; the layers arrive one by one
         models.append(m)
-        caches.append(transformer.KVCache(m, 64))
+        caches.append(transformer.KVCache(m, len(seq)))
         hs.append(m.tok_embed[np.asarray(seq, dtype=np.int64)])
     for l in range(shape.n_layers):
-        w = _np_layer(shape, cfg.seed_target, l)
+        w = _np_layer(shape, seed, l)
         for i, m in enumerate(models):
             hs[i] = transformer.layer_forward(m, caches[i], l, w, hs[i], 0)
         del w
@@ -319,19 +305,39 @@ def test_full_depth_target_against_the_oracle_layer_by_layer(full_depth_pair):
             d = float(np.abs(hs[1] - hs[0]).max() / np.abs(hs[0]).max())
             print(f"  oracle layer {l + 1}/{shape.n_layers}: residual streams of the two oracles differ by {d:.2e} of "
                   f"the largest entry", flush=True)
-    r32, r16 = transformer.head(models[0], hs[0]), transformer.head(models[1], hs[1])
-    rows = slice(len(prompt) - 1, len(seq))             # the frontier's row and the seven after it
+    return transformer.head(models[0], hs[0]), transformer.head(models[1], hs[1])
+
+
+@pytest.mark.parametrize("which", ["target", "draft"])
+def test_full_depth_models_against_the_oracle_layer_by_layer(full_depth_pair, which):
+    """The 80-layer 70B-shape target itself (and the 32-layer 7B-shape draft model) against the oracle.  The fp32
+    oracle cannot hold 70e9 weights at once, but it can take them one layer at a time: the test generates layer l
+    again (same generator, same seeds), runs oracle.transformer.layer_forward for the plain fp32 oracle and for the
+    oracle with bf16 activations, and drops the layer.  One causal pass over the whole sequence (32 prompt tokens, the
+    frontier, 7 more tokens) gives the oracle's logits of the rows the library then computes as a one-token and a
+    seven-token forward - after either prompt path.  In a random-init network of these widths bf16 activation
+    rounding grows with depth (the two oracles part by eoo, no library involved); the library must be no further
+    from the fp32 oracle than that, within a factor - a mistake in any layer (a wrong gain vector, a misplaced head,
+    a stale cache row) gives errors of the order of the logit range itself."""
+    amd, harness, cfg, target, draft = full_depth_pair
+    shape, seed, model = (cfg.target, cfg.seed_target, target) if which == "target" else (cfg.draft, cfg.seed_draft, draft)
+    prompt = synth.prompt_tokens(33, shape.vocab, 41).tolist()
+    extra = synth.prompt_tokens(7, shape.vocab, 42).tolist()
+    r32, r16 = _streamed_oracle_logits(shape, seed, prompt + extra)
+    rows = slice(len(prompt) - 1, len(prompt) + len(extra))     # the frontier's row and the seven after it
     eoo = _rel_err(r16[rows], r32[rows])
-    ctx = harness.make_context(cfg, target, draft, 8, temperature=0.0)
+    # the model in question sits in the context's target slot: spec_verify returns its logits
+    cfg_m = synth.PairConfig(cfg.name, shape, cfg.draft, n_prompt=64, n_generate=32, gamma=7)
+    ctx = harness.make_context(cfg_m, model, draft, 8, temperature=0.0)
     for mode, label in ((0, "chunked prompt pass"), (1, "dense prompt pass")):
         ctx.set_option(amd.SPEC_OPT_PREFILL, mode)
         ctx.prefill(prompt)
         got = np.concatenate([ctx.verify([prompt[-1]], want_logits=True), ctx.verify(extra, want_logits=True)])
         e32, e16 = _rel_err(got, r32[rows]), _rel_err(got, r16[rows])
         agree = int((got.argmax(-1) == r32[rows].argmax(-1)).sum())
-        print(f"  80 layers, {label}: library vs fp32 oracle {e32:.2e}, library vs bf16-activation oracle {e16:.2e}, "
-              f"bf16-activation oracle vs fp32 oracle {eoo:.2e} (max |dlogit| / row range); arg-max equal to the "
-              f"fp32 oracle's in {agree} of 8 rows", flush=True)
+        print(f"  {which}, {shape.n_layers} layers, {label}: library vs fp32 oracle {e32:.2e}, library vs "
+              f"bf16-activation oracle {e16:.2e}, bf16-activation oracle vs fp32 oracle {eoo:.2e} (max |dlogit| / row "
+              f"range); arg-max equal to the fp32 oracle's in {agree} of 8 rows", flush=True)
         assert e32 <= 1.5 * eoo + 2e-3, (label, e32, eoo)
         assert e16 <= 1.5 * eoo + 2e-3, (label, e16, eoo)
     ctx.close()
