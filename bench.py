@@ -36,6 +36,8 @@ def parse():
     ap.add_argument("--depth", type=int, default=0, help="truncate the target to this many layers (experiments)")
     ap.add_argument("--draft-depth", type=int, default=0)
     ap.add_argument("--wgs", type=int, default=-1, help="projection workgroups per CU: -1 auto, 1, 2")
+    ap.add_argument("--tail", type=int, default=-1,
+                    help="SPEC_OPT_TARGET_TAIL_LAYERS: -1 = balanced by the library at run time, n = fixed (experiments)")
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the benchmark line: tokens/s of PEARL and SD over window sizes and acceptance rates")
     ap.add_argument("--sweep-part", default="all", help="with --sweep: all | gamma | cu (which part of the study to run)")
@@ -274,6 +276,7 @@ def main():
     log(f"[bench] built {cfg.name}: target {target.nbytes() / 1e9:.2f} GB, draft {draft.nbytes() / 1e9:.2f} GB in {t_build:.1f}s")
     ctx = harness.make_context(cfg, target, draft, gamma_max, extra_seq=64)
     ctx.set_option(amd.SPEC_OPT_GEMM_WGS_PER_CU, args.wgs)
+    ctx.set_option(amd.SPEC_OPT_TARGET_TAIL_LAYERS, args.tail)
     if args.fuse >= 0:
         ctx.set_option(amd.SPEC_OPT_FUSE_SINGLE, args.fuse)
     prompt = synth.prompt_tokens(cfg.n_prompt, cfg.target.vocab, cfg.seed_prompt).tolist()
@@ -391,6 +394,7 @@ def main():
              "post_fraction": st["post_steps"] / st["steps"], "step_ms": elapsed / st["steps"] * 1e3,
              "step_GBps": bw(step_bytes, elapsed / st["steps"]),
              "overlap_efficiency": (gamma * t_d + (t_vg if st["post_steps"] else t_v1)) / (elapsed / st["steps"])}
+    pearl["target_tail_layers"] = ctx.get_option(amd.SPEC_OPT_TARGET_TAIL_LAYERS)
     log(f"[bench] PEARL: {value:.2f} tok/s, {json.dumps({k: round(v, 3) for k, v in pearl.items()})}")
 
     side = {}

@@ -300,6 +300,13 @@ int spec_accept_rows_static(const float* p_logits_dev, int n_rows, const float* 
  * prologue (residual add + norm input, SiLU * mul); 0 = the ten-kernel chain that forwards over several tokens use.
  * Same operations, sums in the same order up to the grouping of the sums of squares (results agree to fp32
  * rounding, not bit for bit).
+ * SPEC_OPT_TARGET_TAIL_LAYERS: while the two models overlap with one projection workgroup per CU and stream (PEARL
+ * loops from gamma 6 on, or SPEC_OPT_GEMM_WGS_PER_CU = 1), the last n layers of a target forward (rounded to whole
+ * launch chunks of the forward) and its LM head launch with two: the chain that would end later gets the larger share
+ * of the memory pipe, and what is left of it after the draft chain has ended runs at the full rate.  -1 (default):
+ * spec_generate's PEARL loops move n by one chunk per step from where the two chains of the last step ended (the
+ * balance the window size of Section 4.4.1 aims at, reached here at run time); n >= 0: fixed.  The results do not
+ * depend on it (the K split of a projection is the same in both launch modes).  spec_get_option reads the n in use.
  * SPEC_OPT_GUESS_TOKENS: most guesses k a pre-verify step of algo 5 feeds behind the frontier; -1 (default) =
  * gamma - 1, the most that can be used; values above gamma - 1 are clipped.
  * SPEC_OPT_TEST_FAIL_PREFILL (tests of the error path only): n > 0 makes the next spec_prefill give up with
@@ -307,7 +314,7 @@ int spec_accept_rows_static(const float* p_logits_dev, int n_rows, const float* 
  * spec_get_option reads a value back; for SPEC_OPT_GEMM_WGS_PER_CU it is the mode the next forward launches with
  * (1 or 2). */
 enum { SPEC_OPT_GEMM_WGS_PER_CU = 1, SPEC_OPT_GRAPHS = 2, SPEC_OPT_PREFILL = 3, SPEC_OPT_TEST_FAIL_PREFILL = 4,
-       SPEC_OPT_FUSE_SINGLE = 5, SPEC_OPT_GUESS_TOKENS = 6 };
+       SPEC_OPT_FUSE_SINGLE = 5, SPEC_OPT_GUESS_TOKENS = 6, SPEC_OPT_TARGET_TAIL_LAYERS = 7 };
 int spec_set_option(spec_ctx* ctx, int option, int value);
 int spec_get_option(const spec_ctx* ctx, int option, int* value);
 

@@ -27,6 +27,7 @@ SPEC_OPT_PREFILL = 3
 SPEC_OPT_TEST_FAIL_PREFILL = 4
 SPEC_OPT_FUSE_SINGLE = 5
 SPEC_OPT_GUESS_TOKENS = 6
+SPEC_OPT_TARGET_TAIL_LAYERS = 7
 EPI_STORE, EPI_RESID, EPI_SWIGLU = 0, 1, 2
 
 

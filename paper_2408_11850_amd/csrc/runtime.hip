@@ -33,6 +33,9 @@ extern "C" const char* spec_last_error(void) { return g_err; }
     return (code);             \
   } while (0)
 
+#define SPEC_GRAPH_PARTS 24                          // graphs a forward may be cut into (see ModelRt::graphs)
+#define SPEC_TAIL_CHUNKS_MAX (SPEC_GRAPH_PARTS - 2)
+
 namespace {
 
 struct ModelRt {
@@ -58,8 +61,9 @@ struct ModelRt {
   float *partials = nullptr, *opart = nullptr, *mlpart = nullptr, *logits = nullptr;
   long long n_forwards = 0;
   int split_tokens = 0;           // context length the attention split count is sized for (fixed per context)
-  // captured forwards, keyed [tokens][logit mode 0/1/2][projection workgroups per CU][first layers / the rest]
-  hipGraphExec_t graphs[SPEC_MAX_TOKENS + 1][3][3][2] = {};
+  // captured forwards, keyed [tokens][logit mode 0/1/2][projection workgroups per CU][part]; part 0 = the first
+  // layers, 1 = all the rest, 2 + i = chunk i of the rest (forwards whose trailing chunks launch in another mode)
+  hipGraphExec_t graphs[SPEC_MAX_TOKENS + 1][3][3][SPEC_GRAPH_PARTS] = {};
   // activation buffers of the dense prompt path, allocated at its first use for pf_cap tokens
   int pf_cap = 0;
   int* pf_tok = nullptr;
@@ -102,6 +106,10 @@ struct spec_ctx {
   bool use_graphs = true;         // replay captured forwards instead of launching ~10 kernels per layer
   int wgs_opt = -1;               // projection workgroups per CU: -1 = automatic, 1, 2
   int wgs = 2;                    // what the next forward uses
+  int tail_opt = -1;              // trailing target layers that launch with two workgroups per CU while wgs == 1:
+                                  // -1 = chosen by spec_generate from the two chains' end times, >= 0 fixed
+  int tail_layers = 0;            // what the next target forward uses
+  hipEvent_t ev_tend = nullptr, ev_dend = nullptr;   // ends of the target / draft chain of a PEARL step (timed)
   bool fuse_single = true;        // single-token forwards through the projections with fused prologues
   int prefill_opt = -1;           // -1 automatic, 0 = 32-token verify forwards, 1 = dense path
   int fail_prefill_after = 0;     // test hook: > 0 = the next spec_prefill gives up after that many forwards
@@ -398,6 +406,14 @@ int enqueue_forward_single(spec_ctx* c, int which, int logit_rows, int l0, int l
   return SPEC_OK;
 }
 
+// Layers per chunk when a forward is cut into chunks behind its first layers (0: the model is too shallow to cut).
+int tail_chunk_layers(int L) {
+  const int Lh = L >= 8 ? 4 : L;
+  if (Lh >= L) return 0;
+  const int ch = (L - Lh + SPEC_TAIL_CHUNKS_MAX - 1) / SPEC_TAIL_CHUNKS_MAX;
+  return ch < 4 ? 4 : ch;
+}
+
 // One forward of model `which` over M tokens.  logit_rows: 0 = none (prefill), 1 = last row only, M = all rows.
 int forward(spec_ctx* c, int which, const TokenSrc& src, int logit_rows) {
   ModelRt& m = c->m[which];
@@ -408,38 +424,75 @@ int forward(spec_ctx* c, int which, const TokenSrc& src, int logit_rows) {
   hipStream_t st = m.stream;
   HIPCHK(launch_gather_tokens(m.tok_in, c->ring, src, st));
   const int L = m.d.n_layers;
-  if (c->use_graphs && !(c->profile_flags & 1)) {
-    const int lm = logit_rows == 0 ? 0 : (logit_rows >= M ? 2 : 1);
-    // Two graphs per forward: launching ~10 nodes per layer costs the host about 0.45 us per node (0.45 ms for the
-    // 80-layer target), during which the stream would sit idle; a short graph of the first layers is on the GPU in
-    // tens of microseconds and runs while the host launches the rest.
-    const int Lh = L >= 8 ? 4 : L;
-    for (int part = 0; part < (Lh < L ? 2 : 1); ++part) {
-      hipGraphExec_t& ge = m.graphs[M][lm][c->wgs][part];
+  // Cut of the layers into launch units.  Two graphs per forward: launching ~10 nodes per layer costs the host
+  // about 0.45 us per node (0.45 ms for the 80-layer target), during which the stream would sit idle; a short graph
+  // of the first layers is on the GPU in tens of microseconds and runs while the host launches the rest.
+  // While draft and target overlap with one projection workgroup per CU and stream, the target's last layers may
+  // launch with two (tail_layers): the chain that would end later is favoured, and once the draft chain has
+  // ended the target has the GPU to itself, where one workgroup per CU streams at half the rate.  The rest is
+  // then cut into chunks so that the boundary can move without capturing anything again.  The K split of a
+  // projection does not depend on the launch mode, so the numbers are the same bit for bit.
+  const int Lh = L >= 8 ? 4 : L;
+  struct Unit { int l0, l1, wgs, part; } units[SPEC_GRAPH_PARTS];
+  int n_units = 0;
+  units[n_units++] = Unit{0, Lh, c->wgs, 0};
+  const int tail = (which == SPEC_TARGET && c->wgs == 1 && Lh < L) ? c->tail_layers : 0;
+  if (Lh < L && tail <= 0) {
+    units[n_units++] = Unit{Lh, L, c->wgs, 1};
+  } else if (Lh < L) {
+    const int ch = tail_chunk_layers(L);
+    const int tail_from = L - tail;       // chunks that start at or behind this layer launch with two workgroups per CU
+    for (int l0 = Lh, i = 0; l0 < L; l0 += ch, ++i)
+      units[n_units++] = Unit{l0, l0 + ch < L ? l0 + ch : L, l0 >= tail_from ? 2 : 1, 2 + i};
+  }
+  const int wgs_saved = c->wgs;
+  rc = SPEC_OK;
+  for (int u = 0; u < n_units && !rc; ++u) {
+    const Unit& un = units[u];
+    c->wgs = un.wgs;
+    if (c->use_graphs && !(c->profile_flags & 1)) {
+      const int lm = logit_rows == 0 ? 0 : (logit_rows >= M ? 2 : 1);
+      hipGraphExec_t& ge = m.graphs[M][lm][un.wgs][un.part];
       if (!ge) {
-        HIPCHK(hipStreamBeginCapture(st, hipStreamCaptureModeRelaxed));
-        rc = single_token_path(c, m, M) ? enqueue_forward_single(c, which, logit_rows, part ? Lh : 0, part ? L : Lh)
-                                        : enqueue_forward(c, which, M, logit_rows, part ? Lh : 0, part ? L : Lh);
+        hipError_t e = hipStreamBeginCapture(st, hipStreamCaptureModeRelaxed);
+        if (e != hipSuccess) {
+          spec_set_error("hipStreamBeginCapture failed: %s", hipGetErrorString(e));
+          rc = SPEC_E_HIP;
+          break;
+        }
+        rc = single_token_path(c, m, M) ? enqueue_forward_single(c, which, logit_rows, un.l0, un.l1)
+                                        : enqueue_forward(c, which, M, logit_rows, un.l0, un.l1);
         hipGraph_t g = nullptr;
-        hipError_t e = hipStreamEndCapture(st, &g);   // always leave capture mode, also after a failed launch
+        e = hipStreamEndCapture(st, &g);   // always leave capture mode, also after a failed launch
         if (rc || e != hipSuccess) {
           if (g) (void)hipGraphDestroy(g);
-          if (!rc) FAIL(SPEC_E_HIP, "hipStreamEndCapture failed: %s", hipGetErrorString(e));
-          return rc;
+          if (!rc) {
+            spec_set_error("hipStreamEndCapture failed: %s", hipGetErrorString(e));
+            rc = SPEC_E_HIP;
+          }
+          break;
         }
         e = hipGraphInstantiate(&ge, g, nullptr, nullptr, 0);
         (void)hipGraphDestroy(g);
         if (e != hipSuccess) {
           ge = nullptr;
-          FAIL(SPEC_E_HIP, "hipGraphInstantiate failed: %s", hipGetErrorString(e));
+          spec_set_error("hipGraphInstantiate failed: %s", hipGetErrorString(e));
+          rc = SPEC_E_HIP;
+          break;
         }
       }
-      HIPCHK(hipGraphLaunch(ge, st));
+      hipError_t e = hipGraphLaunch(ge, st);
+      if (e != hipSuccess) {
+        spec_set_error("hipGraphLaunch failed: %s", hipGetErrorString(e));
+        rc = SPEC_E_HIP;
+      }
+    } else {
+      rc = single_token_path(c, m, M) ? enqueue_forward_single(c, which, logit_rows, un.l0, un.l1)
+                                      : enqueue_forward(c, which, M, logit_rows, un.l0, un.l1);
     }
-  } else if ((rc = single_token_path(c, m, M) ? enqueue_forward_single(c, which, logit_rows, 0, L)
-                                              : enqueue_forward(c, which, M, logit_rows, 0, L))) {
-    return rc;
   }
+  c->wgs = wgs_saved;
+  if (rc) return rc;
   m.len += M;
   m.n_forwards++;
   return SPEC_OK;
@@ -557,6 +610,8 @@ extern "C" int spec_init(const spec_config* cfg, const spec_model_desc* target, 
     hipError_t e = hipMemset(c->ring, 0, SPEC_RING_MAX * sizeof(int));
     if (e == hipSuccess) e = hipHostMalloc((void**)&c->res_host, sizeof(AcceptResult), hipHostMallocDefault);
     for (int i = 0; i < c->ring_n && e == hipSuccess; ++i) e = hipEventCreateWithFlags(&c->ev_slot[i], hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreate(&c->ev_tend);
+    if (e == hipSuccess) e = hipEventCreate(&c->ev_dend);
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) {
       spec_set_error("context set-up failed: %s", hipGetErrorString(e));
@@ -584,6 +639,8 @@ extern "C" void spec_free(spec_ctx* c) {
   for (int i = 0; i < SPEC_RING_MAX; ++i)
     if (c->ev_slot[i]) (void)hipEventDestroy(c->ev_slot[i]);
   if (c->prof.dev) (void)hipFree(c->prof.dev);
+  if (c->ev_tend) (void)hipEventDestroy(c->ev_tend);
+  if (c->ev_dend) (void)hipEventDestroy(c->ev_dend);
   delete c;
 }
 
@@ -1059,6 +1116,12 @@ extern "C" int spec_generate(spec_ctx* c, int algo, int gamma, int n_generate, i
       for (int i = 0; i < gamma; ++i)
         if ((rc = spec_draft_step(c, u_draft[t * gamma + i], nullptr))) return rc;
     }
+    // where both chains of the step ended (timed events): the balance of the next steps is set from it
+    const bool balance = (algo == 2 || algo == 5) && c->wgs == 1 && c->tail_opt < 0 && c->m[0].stream != c->m[1].stream;
+    if (balance) {
+      HIPCHK(hipEventRecord(c->ev_tend, c->m[SPEC_TARGET].stream));
+      HIPCHK(hipEventRecord(c->ev_dend, c->m[SPEC_DRAFT].stream));
+    }
     if (force_bits && n_test > 0) {
       fm = 0;
       for (int i = 0; i < n_test; ++i)
@@ -1072,6 +1135,20 @@ extern "C" int spec_generate(spec_ctx* c, int algo, int gamma, int n_generate, i
         const int len = c->m[w].len;
         if (len > keep && (rc = rollback_model(c, w, keep))) return rc;
       }
+    if (balance) {
+      // spec_accept has waited for both streams.  Target chain later than the draft chain by more than what one
+      // chunk moves: one more chunk of trailing target layers launches with two workgroups per CU; the other way
+      // round: one fewer.
+      float late_ms = 0.f;
+      const int L = c->m[SPEC_TARGET].d.n_layers, ch = tail_chunk_layers(L);
+      if (ch > 0 && hipEventElapsedTime(&late_ms, c->ev_dend, c->ev_tend) == hipSuccess) {
+        const int most = L - (L >= 8 ? 4 : L);
+        if (late_ms > 0.6f && c->tail_layers + ch <= most) c->tail_layers += ch;
+        else if (late_ms < -0.6f && c->tail_layers >= ch) c->tail_layers -= ch;
+      } else {
+        (void)hipGetLastError();
+      }
+    }
     accepted += n_acc;
     // tokens actually tested: up to and including the first rejection (a pre-verify over guesses may stop earlier
     // without one: keep >= 0 tells a rejection there)
@@ -1363,6 +1440,13 @@ extern "C" int spec_set_option(spec_ctx* c, int option, int value) {
     c->prefill_opt = value;
     return SPEC_OK;
   }
+  if (option == SPEC_OPT_TARGET_TAIL_LAYERS) {
+    if (value < -1) FAIL(SPEC_E_INVAL, "SPEC_OPT_TARGET_TAIL_LAYERS takes -1 or a layer count");
+    const int L = c->m[SPEC_TARGET].d.n_layers, most = L - (L >= 8 ? 4 : L);
+    c->tail_opt = value;
+    c->tail_layers = value < 0 ? 0 : (value > most ? most : value);
+    return SPEC_OK;
+  }
   if (option == SPEC_OPT_GUESS_TOKENS) {
     if (value < -1 || value > SPEC_MAX_TOKENS - 2) FAIL(SPEC_E_INVAL, "SPEC_OPT_GUESS_TOKENS takes -1 or 0..%d", SPEC_MAX_TOKENS - 2);
     c->guess_opt = value;
@@ -1385,6 +1469,7 @@ extern "C" int spec_get_option(const spec_ctx* c, int option, int* value) {
     case SPEC_OPT_FUSE_SINGLE: *value = c->fuse_single ? 1 : 0; return SPEC_OK;
     case SPEC_OPT_TEST_FAIL_PREFILL: *value = c->fail_prefill_after; return SPEC_OK;
     case SPEC_OPT_GUESS_TOKENS: *value = c->guess_opt; return SPEC_OK;
+    case SPEC_OPT_TARGET_TAIL_LAYERS: *value = c->tail_layers; return SPEC_OK;   // what the next target forward uses
   }
   FAIL(SPEC_E_INVAL, "unknown option %d", option);
 }

@@ -419,3 +419,36 @@ def test_sampled_loops_at_the_benchmark_context_length(algo):
     assert k >= 4
     assert ctx.kv_len(amd.SPEC_TARGET) == ctx.committed_len() - 1
     ctx.close()
+
+
+def test_trailing_target_layers_at_two_workgroups_change_timing_only():
+    """While the two models overlap with one projection workgroup per CU and stream, the target's last layers may
+    launch with two (SPEC_OPT_TARGET_TAIL_LAYERS; by default the PEARL loop moves that boundary from where the two
+    chains of the last step ended).  The forward is then cut into more graphs, but the K split of a projection is the
+    same in both launch modes: every setting must commit the same tokens, bit for bit."""
+    import paper_2408_11850_amd as amd
+    from paper_2408_11850_amd import harness
+    shape = synth.ModelShape(12, 256, 4, 4, 688, 1024)
+    cfg = synth.PairConfig("deep_tiny", shape, synth._truncate(shape, 1), draft_from_target_layers=1, dtype="fp32",
+                           n_prompt=32, n_generate=64, gamma=6, logit_scale=8.0)
+    w = bf16_pair(cfg)
+    target, draft = harness.build_pair(cfg, weights=w)
+    gamma, n_gen = 6, 48
+    prompt = synth.prompt_tokens(cfg.n_prompt, cfg.target.vocab, 17).tolist()
+    uni = NpUniforms(synth.make_uniforms(n_gen + 1, gamma, 23))
+    outs = {}
+    for tail in (0, 4, 8, 100, -1):
+        ctx = harness.make_context(cfg, target, draft, gamma)
+        ctx.set_option(amd.SPEC_OPT_TARGET_TAIL_LAYERS, tail)
+        if tail == 100:
+            assert ctx.get_option(amd.SPEC_OPT_TARGET_TAIL_LAYERS) == 8      # clipped to the layers behind the first graph
+        ctx.prefill(prompt)
+        outs[tail], st = ctx.generate(amd.ALGO_PEARL, gamma, n_gen, uni)       # gamma >= 6: one workgroup per CU and stream
+        assert 0 <= ctx.get_option(amd.SPEC_OPT_TARGET_TAIL_LAYERS) <= 8
+        ctx.close()
+    ctx = harness.make_context(cfg, target, draft, gamma, serial=True)       # one stream, two workgroups per CU throughout
+    ctx.prefill(prompt)
+    ref, _ = ctx.generate(amd.ALGO_PEARL, gamma, n_gen, uni)
+    ctx.close()
+    for tail, out in outs.items():
+        assert out == ref, tail
