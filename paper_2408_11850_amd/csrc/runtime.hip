@@ -109,7 +109,8 @@ struct spec_ctx {
   int tail_opt = -1;              // trailing target layers that launch with two workgroups per CU while wgs == 1:
                                   // -1 = chosen by spec_generate from the two chains' end times, >= 0 fixed
   int tail_layers = 0;            // what the next target forward uses
-  hipEvent_t ev_tend = nullptr, ev_dend = nullptr;   // ends of the target / draft chain of a PEARL step (timed)
+  hipEvent_t ev_t0[2] = {}, ev_tend[2] = {}, ev_dend[2] = {};   // start of a PEARL step, ends of its target / draft chain (timed), two sets in turn
+  bool bal_valid[2] = {false, false};   // set holds a step's three events
   bool fuse_single = true;        // single-token forwards through the projections with fused prologues
   int prefill_opt = -1;           // -1 automatic, 0 = 32-token verify forwards, 1 = dense path
   int fail_prefill_after = 0;     // test hook: > 0 = the next spec_prefill gives up after that many forwards
@@ -610,8 +611,11 @@ extern "C" int spec_init(const spec_config* cfg, const spec_model_desc* target, 
     hipError_t e = hipMemset(c->ring, 0, SPEC_RING_MAX * sizeof(int));
     if (e == hipSuccess) e = hipHostMalloc((void**)&c->res_host, sizeof(AcceptResult), hipHostMallocDefault);
     for (int i = 0; i < c->ring_n && e == hipSuccess; ++i) e = hipEventCreateWithFlags(&c->ev_slot[i], hipEventDisableTiming);
-    if (e == hipSuccess) e = hipEventCreate(&c->ev_tend);
-    if (e == hipSuccess) e = hipEventCreate(&c->ev_dend);
+    for (int i = 0; i < 2; ++i) {
+      if (e == hipSuccess) e = hipEventCreate(&c->ev_t0[i]);
+      if (e == hipSuccess) e = hipEventCreate(&c->ev_tend[i]);
+      if (e == hipSuccess) e = hipEventCreate(&c->ev_dend[i]);
+    }
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) {
       spec_set_error("context set-up failed: %s", hipGetErrorString(e));
@@ -639,8 +643,11 @@ extern "C" void spec_free(spec_ctx* c) {
   for (int i = 0; i < SPEC_RING_MAX; ++i)
     if (c->ev_slot[i]) (void)hipEventDestroy(c->ev_slot[i]);
   if (c->prof.dev) (void)hipFree(c->prof.dev);
-  if (c->ev_tend) (void)hipEventDestroy(c->ev_tend);
-  if (c->ev_dend) (void)hipEventDestroy(c->ev_dend);
+  for (int i = 0; i < 2; ++i) {
+    if (c->ev_t0[i]) (void)hipEventDestroy(c->ev_t0[i]);
+    if (c->ev_tend[i]) (void)hipEventDestroy(c->ev_tend[i]);
+    if (c->ev_dend[i]) (void)hipEventDestroy(c->ev_dend[i]);
+  }
   delete c;
 }
 
@@ -1053,6 +1060,13 @@ extern "C" int spec_generate(spec_ctx* c, int algo, int gamma, int n_generate, i
   while (produced < n_generate && (max_steps <= 0 || steps < max_steps)) {
     const long long t = steps;
     int n_acc = 0, n_out = 0, next_mode = SPEC_MODE_PRE, keep = -1, kind;
+    // where both chains of the step start and end (timed events): the balance of the next steps is set from it
+    const bool balance = (algo == 2 || algo == 5) && c->wgs == 1 && c->tail_opt < 0 && c->m[0].stream != c->m[1].stream;
+    const int bset = (int)(steps & 1);
+    if (balance) {
+      c->bal_valid[bset] = false;
+      HIPCHK(hipEventRecord(c->ev_t0[bset], c->m[SPEC_TARGET].stream));
+    }
     long long fm = -1;
     int n_test = 0;
     if (algo == 0) {
@@ -1116,11 +1130,10 @@ extern "C" int spec_generate(spec_ctx* c, int algo, int gamma, int n_generate, i
       for (int i = 0; i < gamma; ++i)
         if ((rc = spec_draft_step(c, u_draft[t * gamma + i], nullptr))) return rc;
     }
-    // where both chains of the step ended (timed events): the balance of the next steps is set from it
-    const bool balance = (algo == 2 || algo == 5) && c->wgs == 1 && c->tail_opt < 0 && c->m[0].stream != c->m[1].stream;
     if (balance) {
-      HIPCHK(hipEventRecord(c->ev_tend, c->m[SPEC_TARGET].stream));
-      HIPCHK(hipEventRecord(c->ev_dend, c->m[SPEC_DRAFT].stream));
+      HIPCHK(hipEventRecord(c->ev_tend[bset], c->m[SPEC_TARGET].stream));
+      HIPCHK(hipEventRecord(c->ev_dend[bset], c->m[SPEC_DRAFT].stream));
+      c->bal_valid[bset] = true;
     }
     if (force_bits && n_test > 0) {
       fm = 0;
@@ -1135,16 +1148,30 @@ extern "C" int spec_generate(spec_ctx* c, int algo, int gamma, int n_generate, i
         const int len = c->m[w].len;
         if (len > keep && (rc = rollback_model(c, w, keep))) return rc;
       }
-    if (balance) {
-      // spec_accept has waited for both streams.  Target chain later than the draft chain by more than what one
-      // chunk moves: one more chunk of trailing target layers launches with two workgroups per CU; the other way
-      // round: one fewer.
-      float late_ms = 0.f;
+    if (balance && c->bal_valid[bset ^ 1]) {
+      // The step before this one: both its chains have ended by now (this step's accept waited for a draft that
+      // the draft stream produced behind them), whereas this step's draft chain may still be running - PEARL does
+      // not wait for it.  Target chain later than the draft chain: more trailing target layers launch with two
+      // workgroups per CU; the other way round: fewer.  A chunk that changes mode moves the two ends apart by
+      // 0.4 - 1.3 ms of a 42 ms step (measured on the 70B/7B shapes; a chunk is 1 / 20 of the target chain); the
+      // boundary moves by the lag counted in chunk times, at most 4 chunks a step, which errs on the slow side.
+      // Both ends are timed from the step's start: the time between two events is only defined forwards.
+      const int o = bset ^ 1;
+      c->bal_valid[o] = false;
+      float span_ms = 0.f, draft_ms = 0.f;
       const int L = c->m[SPEC_TARGET].d.n_layers, ch = tail_chunk_layers(L);
-      if (ch > 0 && hipEventElapsedTime(&late_ms, c->ev_dend, c->ev_tend) == hipSuccess) {
-        const int most = L - (L >= 8 ? 4 : L);
-        if (late_ms > 0.6f && c->tail_layers + ch <= most) c->tail_layers += ch;
-        else if (late_ms < -0.6f && c->tail_layers >= ch) c->tail_layers -= ch;
+      if (ch > 0 && hipEventElapsedTime(&span_ms, c->ev_t0[o], c->ev_tend[o]) == hipSuccess &&
+          hipEventElapsedTime(&draft_ms, c->ev_t0[o], c->ev_dend[o]) == hipSuccess && span_ms > 0.f) {
+        const float late_ms = span_ms - draft_ms;             // > 0: the target chain ended later
+        const int most = (L - (L >= 8 ? 4 : L)) / ch * ch;
+        const float unit = span_ms * (float)ch / (float)L;
+        int move = (int)(late_ms / unit);                     // towards zero
+        if (move == 0 && late_ms > 0.3f * unit) move = 1;
+        if (move == 0 && late_ms < -0.3f * unit) move = -1;
+        if (move > 4) move = 4;
+        if (move < -4) move = -4;
+        const int t2 = c->tail_layers + move * ch;
+        c->tail_layers = t2 < 0 ? 0 : (t2 > most ? most : t2);
       } else {
         (void)hipGetLastError();
       }
