@@ -452,3 +452,55 @@ def test_trailing_target_layers_at_two_workgroups_change_timing_only():
     ctx.close()
     for tail, out in outs.items():
         assert out == ref, tail
+
+
+@pytest.mark.parametrize("algo", [1, 2])
+def test_largest_window_takes_the_oracles_decisions(algo):
+    """gamma = 31, the largest window a context takes: vanilla SD verifies 32 rows in one forward (two full row
+    tiles), PEARL's post-verify 31, the ring of pending drafts holds 62 and wraps.  The tiny pair never accepts 31
+    drafts in a row on its own, so the decisions of steps 1, 2, 4 and 5 are scripted to accept everything (steps 0
+    and 3 and all later ones are the pair's own); same lockstep comparison as above."""
+    cfg = synth.config("tiny")
+    amd, harness, target, draft, tm, dm = _pair(cfg)
+    gamma = 31
+    scripted = lambda t: t in (1, 2, 4, 5)
+    force = lambda t, i: True if scripted(t) else None
+
+    def gpu(amd_, ctx, algo_, g, n_generate, uni):
+        steps, mode, produced, t = [], amd_.SPEC_MODE_PRE, 0, 0
+        while produced < n_generate:
+            if algo_ == amd_.ALGO_SD:
+                kind = amd_.SPEC_ACCEPT_SD
+                for i in range(g):
+                    ctx.draft_step(uni.draft[t, i])
+                ctx.verify(n_tokens=g + 1)
+            elif mode == amd_.SPEC_MODE_PRE:
+                kind = amd_.SPEC_ACCEPT_PRE
+                ctx.verify(n_tokens=1)
+                for i in range(g):
+                    ctx.draft_step(uni.draft[t, i])
+            else:
+                kind = amd_.SPEC_ACCEPT_POST
+                ctx.verify(n_tokens=g)
+                for i in range(g):
+                    ctx.draft_step(uni.draft[t, i])
+            fm = (1 << (g + 1)) - 1 if scripted(t) else -1
+            res = ctx.accept(kind, uni.accept[t, :g + 1], uni.resample[t], fm)
+            if res["keep_len"] >= 0:
+                for w in (amd_.SPEC_TARGET, amd_.SPEC_DRAFT):
+                    if ctx.kv_len(w) > res["keep_len"]:
+                        ctx.rollback_kv(w, res["keep_len"])
+            steps.append({"mode": mode, "tokens": res["tokens"], "n_accepted": res["n_accepted"]})
+            produced += len(res["tokens"])
+            mode = res["next_mode"]
+            t += 1
+        return steps
+
+    loop = loops.speculative if algo == 1 else loops.pearl
+    oracle = lambda lt, ld, prompt, n, g, uni, **kw: loop(lt, ld, prompt, n, g, uni, force=force, **kw)
+    agreed, splits, wt, wd, modes = lockstep_run(amd, harness, cfg, target, draft, tm, dm, algo, gamma, 1.0,
+                                                 n_total=160, seed=cfg.seed_uniform + 5, oracle_loop=oracle,
+                                                 gpu_steps=gpu, first_segment=160)
+    print(f"algo={algo} gamma=31: {agreed} steps identical, {splits} splits; worst logit error target {wt:.2e} "
+          f"draft {wd:.2e}", flush=True)
+    assert splits <= 1 and agreed >= 8
