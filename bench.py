@@ -41,7 +41,7 @@ def parse():
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the benchmark line: tokens/s of PEARL and SD over window sizes and acceptance rates")
     ap.add_argument("--sweep-part", default="all", help="with --sweep: all | gamma | cu (which part of the study to run)")
-    ap.add_argument("--phase", default="", choices=["", "verify", "verify-graph", "draft"],
+    ap.add_argument("--phase", default="", choices=["", "verify", "verify-graph", "draft", "step-chains"],
                     help="run only that pass alone (N = --steps forwards at the prompt's context length) and print its "
                          "figures: verify = kernel by kernel with an event pair per projection launch, verify-graph / draft = "
                          "captured graphs replayed; the commands the rocprofv3 summaries under profiles/ are made with")
@@ -202,6 +202,49 @@ def sweep(args, cfg, ctx, amd, synth, sync, n0, tp, tq, log):
                       "ar_tokens_per_s": ar[0], "rows": rows, "cu_split_gamma": g, "cu_split": split_rows}))
 
 
+def step_chains(args, cfg, ctx, amd, sync, n0, gamma, log):
+    import torch
+    import synth
+    N = max(4, args.steps)
+    post = args.rows != 1
+    ctx.set_option(amd.SPEC_OPT_GEMM_WGS_PER_CU, 1 if args.wgs < 0 else args.wgs)
+    ctx.set_option(amd.SPEC_OPT_TARGET_TAIL_LAYERS, max(args.tail, 0))
+    uni = synth.make_uniforms(N + 1, gamma, cfg.seed_uniform)
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    mode, rows = amd.SPEC_MODE_PRE, []
+    ctx.rewind(n0)
+    for t in range(N):
+        e0t, e0d, et, ed = ev(), ev(), ev(), [ev() for _ in range(gamma)]
+        sync()
+        e0t.record(ctx.stream_target); e0d.record(ctx.stream_draft)
+        pre = mode == amd.SPEC_MODE_PRE
+        ctx.verify(n_tokens=1 if pre else gamma)
+        et.record(ctx.stream_target)
+        for i in range(gamma):
+            ctx.draft_step(float(uni.draft[t, i])); ed[i].record(ctx.stream_draft)
+        res = ctx.accept(amd.SPEC_ACCEPT_PRE if pre else amd.SPEC_ACCEPT_POST, uni.accept[t, :gamma + 1].numpy(),
+                         float(uni.resample[t]), (1 << (gamma + 1)) - 1 if post else 0)
+        if res["keep_len"] >= 0:
+            for w in (amd.SPEC_TARGET, amd.SPEC_DRAFT):
+                if ctx.kv_len(w) > res["keep_len"]:
+                    ctx.rollback_kv(w, res["keep_len"])
+        sync()
+        rows.append({"mode": "pre" if pre else "post", "target_chain_ms": round(e0t.elapsed_time(et), 2),
+                     "draft_forwards_end_ms": [round(e0d.elapsed_time(e), 2) for e in ed]})
+        mode = res["next_mode"]
+    keep = rows[len(rows) // 2:]                       # the first steps capture graphs
+    avg = lambda xs: round(sum(xs) / len(xs), 2)
+    out = {"phase": "step-chains", "workload": cfg.name, "gamma": gamma, "n_ctx": n0 - 1,
+           "projection_workgroups_per_cu": ctx.get_option(amd.SPEC_OPT_GEMM_WGS_PER_CU),
+           "target_tail_layers": ctx.get_option(amd.SPEC_OPT_TARGET_TAIL_LAYERS), "steps_kept": len(keep),
+           "mode": keep[-1]["mode"], "target_chain_ms": avg([r["target_chain_ms"] for r in keep]),
+           "draft_chain_ms": avg([r["draft_forwards_end_ms"][-1] for r in keep]),
+           "first_draft_forward_ms": avg([r["draft_forwards_end_ms"][0] for r in keep]),
+           "last_step": keep[-1]}
+    log(f"[bench] step-chains: {json.dumps(out)}")
+    print(json.dumps(out))
+
+
 def phase(args, cfg, ctx, amd, sync, n0, gamma, log):
     """One pass alone, N = --steps forwards at the prompt's context length; the commands behind the per-kernel tables
     in profiles/ (run under `rocprofv3 --kernel-trace --stats` or `--pmc ...`, with --gamma given so that no
@@ -209,8 +252,15 @@ def phase(args, cfg, ctx, amd, sync, n0, gamma, log):
       verify        kernel by kernel, every projection launch stamping a HIP event pair with its own start / end:
                     the dominant kernel's average launch duration as bench.py's roofline object measures it
       verify-graph  the same forwards as the library runs them (captured graphs replayed): the pass's wall time
-      draft         draft forwards (with their draws), graphs replayed"""
+      draft         draft forwards (with their draws), graphs replayed
+      step-chains   PEARL steps driven call by call with events on both streams: when the target chain and every
+                    draft forward of a step end (the tracer runs the two streams one after the other, so this is
+                    the untraced view of the overlap); --tail fixes the trailing target layers that launch with
+                    two workgroups per CU, decisions forced to accept (post-verify steps) unless --rows 1
+                    (rejections: pre-verify steps)"""
     N = max(1, args.steps)
+    if args.phase == "step-chains":
+        return step_chains(args, cfg, ctx, amd, sync, n0, gamma, log)
     verify = args.phase.startswith("verify")
     shape = cfg.target if verify else cfg.draft
     out = {"phase": args.phase, "workload": cfg.name, "n_ctx": n0 - 1, "forwards": N, "gamma": gamma}
