@@ -401,11 +401,20 @@ def main():
         alone_stats[k + "_frac_of_peak"] = alone_stats[k + "_GBps"] / HBM_PEAK_GBS
     log(f"[bench] alone: {json.dumps({k: round(v, 3) for k, v in alone_stats.items()})}")
 
-    # streaming-read ceiling of this machine (plain 16-byte loads over the largest weight buffer)
-    buf = target.layers[0]["w_gateup"]
+    # streaming-read ceiling of this machine: plain 16-byte loads over 2 GiB (10 launches back to back between two events,
+    # best of 3): what a long stream reaches; a launch of the projection kernel streams 134 - 940 MB and pays its
+    # ramp and tail on every one of them
+    buf = torch.empty(1 << 30, dtype=torch.bfloat16, device=dev).fill_(1.0)
     amd.read_probe(buf); sync()
-    _, t_rp = timed(lambda: [amd.read_probe(buf) for _ in range(10)], sync)
-    read_ceiling = buf.numel() * 2 * 10 / t_rp / 1e9
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    read_ceiling = 0.0
+    for _ in range(3):
+        e0.record()
+        for _ in range(10):
+            amd.read_probe(buf)
+        e1.record(); sync()
+        read_ceiling = max(read_ceiling, buf.numel() * 2 * 10 / (e0.elapsed_time(e1) * 1e-3) / 1e9)
+    del buf
 
     # ---- the timed region: W warm-up + K timed PEARL steps -------------------------------------
     K, W = args.steps, args.warmup
