@@ -512,15 +512,17 @@ def main():
                      "achieved": gemm_alone, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gemm_alone / HBM_PEAK_GBS,
                      "traffic": traffic, "launches": int(n_a), "avg_launch_us": ms_a / max(n_a, 1) * 1e3,
                      "avg_bytes_per_launch": bytes_a / max(n_a, 1), "read_ceiling_GBps": read_ceiling,
-                     "note": "achieved = weight bytes of the target's projection launches / their HIP-event durations, "
+                     "note": "achieved = weight bytes of the target's projection launches / their durations by the kernel's own "
+                             "wall-clock stamps (first workgroup in to last workgroup out), "
                              "measured in this run over 3 verify forwards (M = gamma, context = the prompt) with the GPU "
                              "to itself: the figure `rocprofv3 --kernel-trace --stats -- python3 bench.py --phase verify` "
                              "reproduces (profiles/verify_alone_70b_7b_kernel_stats.md; the tracer runs the two streams of "
                              "a PEARL step one after the other, so only the stream-alone figure can be traced).  "
                              "in_step_* = the same kernel inside the timed PEARL steps, where it shares the HBM pipe and "
                              "every CU with the draft stream: the K timed steps run a second time (same state, same "
-                             "uniforms, same tokens) with an event pair around every launch, which needs kernel-by-kernel "
-                             "launches and costs instrumented_ms_per_step - ms_per_step.  traffic is not measured in this "
+                             "uniforms, same tokens) with the stamps switched on, which needs kernel-by-kernel "
+                             "launches and costs instrumented_ms_per_step - ms_per_step.  read_ceiling_GBps = plain "
+                             "16-byte loads over 2 GiB, 10 launches between two events, measured in this run.  traffic is not measured in this "
                              "run: it is read from profiles/traffic.json (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on the "
                              "stand-alone projection driver, bytes per launch)",
                      "in_step_achieved": in_step, "in_step_frac": in_step / HBM_PEAK_GBS,
