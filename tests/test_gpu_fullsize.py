@@ -199,6 +199,30 @@ def test_small_pair_at_full_depth_decodes_like_the_oracle(small_pair_full_depth,
         assert agreed >= 12
 
 
+@pytest.mark.parametrize("gamma,k,temperature", [(4, 3, 0.6), (8, 5, 1.0)])
+def test_small_pair_at_full_depth_pre_verifies_several_drafts_like_the_oracle(small_pair_full_depth, gamma, k, temperature):
+    """PEARL with pre-verify over guessed continuations (closing remark of Section 4.3) on the full 24-layer pair, the
+    pair's own decisions (at temperatures 0.6 and 1 it accepts often enough for pre-verify steps to take several drafts), guesses from
+    the caller (the step's drafts, one in three corrupted), in lockstep with the oracle's reading of it."""
+    from tests.test_gpu_loops import lockstep_run
+    from tests.test_gpu_multi_preverify import scripted_hooks
+    from tests.util import EXACT_MARGIN
+    amd, harness, cfg, target, draft, tm, dm, prompt, filled = small_pair_full_depth
+    caches = (_copy_cache(filled[0]), _copy_cache(filled[1]))
+    gpu, oracle, seen = scripted_hooks(k, cfg.target.vocab)
+    agreed, splits, wt, wd, modes = lockstep_run(amd, harness, cfg, target, draft, tm, dm, amd.ALGO_PEARL_GUESS, gamma,
+                                                 temperature, n_total=96, seed=cfg.seed_uniform + 3, prompt=prompt,
+                                                 prefill_mode=1, first_segment=96, oracle_caches=caches,
+                                                 oracle_loop=oracle, gpu_steps=gpu, gpu_first=True)
+    acc_pre = sorted({s["n_accepted"] for s in seen if s["mode"] == amd.SPEC_MODE_PRE})
+    rows_post = sorted({s["rows"] for s in seen if s["mode"] == amd.SPEC_MODE_POST})
+    print(f"gamma={gamma} k={k} T={temperature}: {agreed} steps identical, {splits} splits within {EXACT_MARGIN} of a "
+          f"flip; pre-verify acceptances seen {acc_pre}, post-verify rows seen {rows_post}; worst logit error target "
+          f"{wt:.2e} draft {wd:.2e}", flush=True)
+    assert agreed >= 10 and (temperature == 1.0 or splits <= 1)     # (temperature 1: see the test above)
+    assert max(acc_pre) >= 2 and len(rows_post) >= 2
+
+
 DEPTH_TOL_FP32 = {2: 2e-2, 4: 2e-2, 8: 4e-2}    # against the fp32 oracle: the stated 2e-2 holds up to 4 layers at these widths
 DEPTH_TOL_BF16 = 2e-2                              # against the oracle with bf16 activations, any depth measured
 
