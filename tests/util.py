@@ -61,7 +61,7 @@ def bf16_pair(cfg):
 
 LOGIT_TOL = 2e-2        # max |library - oracle| logit error relative to the row's logit range (bf16 path vs fp32)
 EXACT_MARGIN = 2e-5     # decisions taken from the same fp32 logits may differ only this close to a flip
-#                         (the kernels form exp() with the hardware's exp2 and a reciprocal: relative 1e-5, see DESIGN)
+#                         (the kernels form exp() with the hardware's exp2 and a reciprocal: relative 1e-5)
 
 
 class LockstepModel:
