@@ -446,6 +446,12 @@ def test_trailing_target_layers_at_two_workgroups_change_timing_only():
         outs[tail], st = ctx.generate(amd.ALGO_PEARL, gamma, n_gen, uni)       # gamma >= 6: one workgroup per CU and stream
         assert 0 <= ctx.get_option(amd.SPEC_OPT_TARGET_TAIL_LAYERS) <= 8
         ctx.close()
+    ctx = harness.make_context(cfg, target, draft, gamma)                     # the same cut launched kernel by kernel
+    ctx.set_option(amd.SPEC_OPT_GRAPHS, 0)
+    ctx.set_option(amd.SPEC_OPT_TARGET_TAIL_LAYERS, 4)
+    ctx.prefill(prompt)
+    outs["no graphs"], _ = ctx.generate(amd.ALGO_PEARL, gamma, n_gen, uni)
+    ctx.close()
     ctx = harness.make_context(cfg, target, draft, gamma, serial=True)       # one stream, two workgroups per CU throughout
     ctx.prefill(prompt)
     ref, _ = ctx.generate(amd.ALGO_PEARL, gamma, n_gen, uni)
