@@ -155,3 +155,42 @@ def test_greedy_equals_autoregressive_and_guess_rows_get_used():
     # the target as its own draft: never rejected, one pre-verify step at the start, the same text
     out2 = multi_preverify.pearl_multi_preverify(mk(tm), mk(tm), prompt, n_gen, gamma, k, uni, temperature=0.0)
     assert out2 == ar
+
+
+def test_caches_after_a_sampled_run_equal_a_clean_pass():
+    """The target's cache takes in guessed tokens that are cut off again whenever a draft leaves the guessed path,
+    and both caches are rolled back on every rejection: afterwards they must hold exactly what one clean pass over the
+    committed text produces (a stale guess row or a draft row that survived a rollback would differ), the target
+    lacking the frontier.  Guesses: the step's own continuation under the draft's arg-max, wrong about half the
+    time for a sampled run."""
+    cfg, tm, dm = _tiny_pair()
+    prompt = synth.prompt_tokens(8, cfg.target.vocab, 7).tolist()
+    n_gen, gamma, k = 40, 4, 3
+    uni = NpUniforms(synth.make_uniforms(n_gen + 1, gamma, 99))
+    t, d = transformer.CachedModel(tm, 128), transformer.CachedModel(dm, 128)
+    peek = transformer.CachedModel(dm, 128)
+
+    def guess(committed, kk):            # greedy continuation of the draft model from the committed text
+        peek.rollback(0)
+        lg = peek.feed(committed)[-1]
+        out = []
+        for _ in range(kk):
+            out.append(int(np.argmax(lg)))
+            lg = peek.feed([out[-1]])[0]
+        return out
+
+    tr = []
+    out = multi_preverify.pearl_multi_preverify(t, d, prompt, n_gen, gamma, k, uni, temperature=0.5,
+                                                logit_scale=cfg.logit_scale, trace=tr, guess=guess)
+    assert len(out) == n_gen
+    committed_len = len(prompt) + sum(s["n_committed"] for s in tr)
+    assert t.len == committed_len - 1
+    assert sum(s["guess_rows_used"] for s in tr) >= 1 and any(s["mode"] == loops.POST for s in tr)
+    assert t.n_forwards == len(tr) + 1 and d.n_forwards == gamma * len(tr) + 1      # + the prompt pass of each
+    full = prompt + out
+    for cm, model in ((t, tm), (d, dm)):
+        clean = transformer.CachedModel(model, 128)
+        n_check = min(cm.len, len(full) - 1)
+        clean.feed(full[:n_check])
+        np.testing.assert_allclose(cm.cache.k[:, :n_check], clean.cache.k[:, :n_check], rtol=0, atol=1e-10)
+        np.testing.assert_allclose(cm.cache.v[:, :n_check], clean.cache.v[:, :n_check], rtol=0, atol=1e-10)
