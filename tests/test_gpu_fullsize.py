@@ -289,16 +289,24 @@ def full_depth_pair():
     return amd, harness, cfg, target, draft
 
 
-def _np_layer(shape, seed, l):
+def _np_layer(shape, seed, l, stage):
     """Layer l of the generator's weights as fp32 NumPy arrays (the bf16 values, upcast): made on the GPU by the same
-    counter-based generator that filled the library's model, one layer at a time."""
+    counter-based generator that filled the library's model, one layer at a time.  `stage`: dict of pinned host
+    tensors, one per matrix, reused from layer to layer (a pageable copy of 3.4 GB per layer is what this test
+    would otherwise spend most of its time on); the arrays returned are views of them, valid until the next call."""
     import torch
-    cv = lambda t: np.ascontiguousarray(t.float().cpu().numpy())
     lay = {}
+
+    def cv(name, t):
+        if name not in stage:
+            stage[name] = torch.empty(t.shape, dtype=torch.float32, pin_memory=True)
+        stage[name].copy_(t.float())
+        return stage[name].numpy()
+
     for name in ("attn_norm", "ffn_norm"):
-        lay[name] = cv(synth.gain_tensor(shape.d_model, seed, 16 * l + synth._SLOT[name], torch.bfloat16, "cuda"))
+        lay[name] = cv(name, synth.gain_tensor(shape.d_model, seed, 16 * l + synth._SLOT[name], torch.bfloat16, "cuda"))
     for name, shp in synth.layer_matrix_shapes(shape).items():
-        lay[name] = cv(synth.normal_tensor(shp, 0.02, seed, 16 * l + synth._SLOT[name], torch.bfloat16, "cuda"))
+        lay[name] = cv(name, synth.normal_tensor(shp, 0.02, seed, 16 * l + synth._SLOT[name], torch.bfloat16, "cuda"))
     return lay
 
 
@@ -320,8 +328,9 @@ def _streamed_oracle_logits(shape, seed, seq):
         models.append(m)
         caches.append(transformer.KVCache(m, len(seq)))
         hs.append(m.tok_embed[np.asarray(seq, dtype=np.int64)])
+    stage = {}
     for l in range(shape.n_layers):
-        w = _np_layer(shape, seed, l)
+        w = _np_layer(shape, seed, l, stage)
         for i, m in enumerate(models):
             hs[i] = transformer.layer_forward(m, caches[i], l, w, hs[i], 0)
         del w
@@ -337,7 +346,7 @@ def test_full_depth_models_against_the_oracle_layer_by_layer(full_depth_pair, wh
     """The 80-layer 70B-shape target itself (and the 32-layer 7B-shape draft model) against the oracle.  The fp32
     oracle cannot hold 70e9 weights at once, but it can take them one layer at a time: the test generates layer l
     again (same generator, same seeds), runs oracle.transformer.layer_forward for the plain fp32 oracle and for the
-    oracle with bf16 activations, and drops the layer.  One causal pass over the whole sequence (32 prompt tokens, the
+    oracle with bf16 activations, and drops the layer.  One causal pass over the whole sequence (96 prompt tokens, the
     frontier, 7 more tokens) gives the oracle's logits of the rows the library then computes as a one-token and a
     seven-token forward - after either prompt path.  In a random-init network of these widths bf16 activation
     rounding grows with depth (the two oracles part by eoo, no library involved); the library must be no further
@@ -345,13 +354,13 @@ def test_full_depth_models_against_the_oracle_layer_by_layer(full_depth_pair, wh
     a stale cache row) gives errors of the order of the logit range itself."""
     amd, harness, cfg, target, draft = full_depth_pair
     shape, seed, model = (cfg.target, cfg.seed_target, target) if which == "target" else (cfg.draft, cfg.seed_draft, draft)
-    prompt = synth.prompt_tokens(33, shape.vocab, 41).tolist()
+    prompt = synth.prompt_tokens(97, shape.vocab, 41).tolist()      # 96 cached positions: two K/V pages, three chunks
     extra = synth.prompt_tokens(7, shape.vocab, 42).tolist()
     r32, r16 = _streamed_oracle_logits(shape, seed, prompt + extra)
     rows = slice(len(prompt) - 1, len(prompt) + len(extra))     # the frontier's row and the seven after it
     eoo = _rel_err(r16[rows], r32[rows])
     # the model in question sits in the context's target slot: spec_verify returns its logits
-    cfg_m = synth.PairConfig(cfg.name, shape, cfg.draft, n_prompt=64, n_generate=32, gamma=7)
+    cfg_m = synth.PairConfig(cfg.name, shape, cfg.draft, n_prompt=128, n_generate=32, gamma=7)
     ctx = harness.make_context(cfg_m, model, draft, 8, temperature=0.0)
     for mode, label in ((0, "chunked prompt pass"), (1, "dense prompt pass")):
         ctx.set_option(amd.SPEC_OPT_PREFILL, mode)
